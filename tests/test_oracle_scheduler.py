@@ -1,0 +1,238 @@
+"""Pins for oracle/scheduler.py: invariants, closed forms and hand-derived cases."""
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle import (EOS_NATURAL_OR_FORCED, HARVESTED, MODE_ONPOLICY, MODE_PARTIAL, MODE_SYNC, OracleModel,
+                    OracleRollout, PagedKV, splitmix64_permutation)
+
+
+def _mk(L, Q, n_pages=10_000, P=5, pt=16, cap=10_000, **kw):
+    o = OracleRollout(max_slots=Q, page_tokens=pt, n_pages=n_pages, max_new_tokens=cap, eos_id=99, **kw)
+    o.submit([np.arange(P, dtype=np.int32)] * len(L), L)
+    return o
+
+
+def _lengths(n, seed, cap=300):
+    return W.make_target_lengths(n, 3.5, 0.9, cap, seed)
+
+
+def test_bubble_ratio_worked_example_of_eq4():
+    """Eq. 4 by hand: Q = 4, one step each with r = 4, 4, 3, 1 -> (0+0+1+3) / (4*4) = 0.25.
+    Lengths 2, 3, 3, 4 in four slots produce exactly that occupancy."""
+    o = _mk([2, 3, 3, 4], Q=4)
+    o.run_to_completion(4)
+    assert o.step_no == 4 and o.idle == 4
+    assert o.bubble_ratio() == 0.25
+
+
+def test_every_rollout_harvested_exactly_once_and_groups_are_ordered():
+    L = _lengths(200, 1)
+    o = _mk(L, Q=16)
+    groups = o.run_to_completion(8)
+    ids = [s.seq_id for g in groups for s in g]
+    assert sorted(ids) == list(range(200))
+    keys = [(s.completion_step, s.gen_len, s.seq_id) for g in groups for s in g]
+    assert keys == sorted(keys)
+    assert all(len(g) == 8 for g in groups)
+    assert all(s.state == HARVESTED for s in o.seqs)
+    assert [s.gen_len for s in o.seqs] == list(L)
+    assert all(s.tokens[-1] == 99 and 99 not in s.tokens[:-1] for s in o.seqs)
+    st = o.stats()
+    assert st["busy"] == st["gen_tokens"] == int(L.sum())          # every phase-B execution emits one token
+    assert st["busy"] + st["idle"] == 16 * st["steps"]
+
+
+def test_sync_baseline_bubble_closed_form():
+    """No refill until the batch drains: bubble = 1 - sum L / (Q * sum_b max L_b) exactly."""
+    L = _lengths(64, 2)
+    Q = 16
+    o = _mk(L, Q=Q, mode=MODE_SYNC)
+    o.run_to_completion(Q)
+    steps = sum(int(L[b:b + Q].max()) for b in range(0, 64, Q))
+    assert o.step_no == steps
+    assert o.idle == Q * steps - int(L.sum())
+    # one batch: 1 - sum L / (Q max L)
+    o1 = _mk(L[:Q], Q=Q, mode=MODE_SYNC)
+    o1.run_to_completion(Q)
+    assert abs(o1.bubble_ratio() - (1 - L[:Q].sum() / (Q * L[:Q].max()))) < 1e-15
+
+
+def test_enough_slots_means_completion_step_is_length_minus_one_and_harvest_is_the_length_sort():
+    L = _lengths(40, 3)
+    o = _mk(L, Q=64)
+    groups = o.run_to_completion(5)
+    assert all(s.completion_step == L[s.seq_id] - 1 for s in o.seqs)
+    order = [s.seq_id for g in groups for s in g]
+    assert order == sorted(range(40), key=lambda i: (L[i], i))
+
+
+def test_refill_happens_the_step_after_a_slot_frees_and_takes_the_lowest_slot():
+    # Q = 2; seq0 L=1 finishes at step 0, seq1 L=3; seq2 must enter slot 0 at step 1.
+    o = _mk([1, 3, 2, 2], Q=2)
+    i0 = o.step()
+    assert i0["admitted"] == [(0, 0), (1, 1)] and i0["finished"] == [0] and i0["r"] == 2
+    i1 = o.step()
+    assert i1["admitted"] == [(2, 0)] and i1["r"] == 2
+    i2 = o.step()                                                  # seq1 (L=3) and seq2 (L=2) finish together
+    assert sorted(i2["finished"]) == [1, 2] and i2["admitted"] == []
+    i3 = o.step()
+    assert i3["admitted"] == [(3, 0)] and i3["r"] == 1
+    g = o.harvest(2)
+    assert [[s.seq_id for s in x] for x in g] == [[0, 2]]          # (0,1,0) then (2,2,2) before (2,3,1)
+
+
+def test_no_slot_is_idle_while_the_queue_is_non_empty():
+    o = _mk(_lengths(300, 4), Q=8)
+    o.run_to_completion(4)
+    assert o.idle_q == 0 and o.steps_q > 0
+
+
+def test_harvest_timing_independence_without_staleness():
+    L = _lengths(120, 5)
+    a = _mk(L, Q=8)
+    ga = a.run_to_completion(6)
+    b = _mk(L, Q=8)
+    while b.queue or any(x is not None for x in b.slots):
+        b.step()
+    gb = b.harvest(6, flush=True)
+    assert [[s.seq_id for s in g] for g in ga] == [[s.seq_id for s in g] for g in gb]
+
+
+def test_page_conservation_and_slot_exclusivity_every_step():
+    L = _lengths(60, 6, cap=120)
+    o = _mk(L, Q=6, n_pages=40, P=20, pt=4, max_staleness=1)
+    while o.queue or any(x is not None for x in o.slots):
+        o.step()
+        held = [p for s in o.slots if s is not None for p in s.pages]
+        assert len(held) + len(o.free) == 40
+        assert len(set(held) | set(o.free)) == 40
+        live = [s.seq_id for s in o.slots if s is not None]
+        assert len(live) == len(set(live))
+        for s in o.slots:
+            if s is not None:                                      # pages cover the next write position
+                assert (len(s.prompt) + s.gen_len - 1) // 4 < len(s.pages)
+        if len(o.finished) >= 3:
+            o.harvest(3)
+    o.harvest(3, flush=True)
+    assert all(s.state == HARVESTED for s in o.seqs)
+    assert [s.gen_len for s in o.seqs] == list(L)
+
+
+def test_preemption_victim_rule_hand_built():
+    """3 slots, 4-token pages, 4 pages, prompts of 3 tokens, every L = 10.
+    Step 0: three admissions take 3 pages (1 free).  Step 1: all reach gen_len 2 and need page 1;
+    slot 0 takes the last free page; slot 1 finds the pool empty -> victim = smallest gen_len, ties to the
+    largest seq_id = seq 2, whose single page goes to slot 1.  Seq 2 waits at the queue front."""
+    o = _mk([10, 10, 10], Q=3, n_pages=4, P=3, pt=4)
+    assert o.step()["preempted"] == []
+    i1 = o.step()
+    assert i1["preempted"] == [2] and i1["n_active"] == 2 and i1["n_queued"] == 1 and i1["free_pages"] == 0
+    assert o.seqs[2].gen_len == 2 and o.seqs[2].n_preempt == 1
+    groups = o.run_to_completion(3)
+    assert [s.gen_len for s in o.seqs] == [10, 10, 10]
+    assert sorted(s.seq_id for g in groups for s in g) == [0, 1, 2]
+    assert o.seqs[2].completion_step > max(o.seqs[0].completion_step, o.seqs[1].completion_step)
+    st = o.stats()
+    assert st["busy"] == st["gen_tokens"] == 30                    # preemption discards nothing
+    assert st["prefill_tokens"] > 9                                # re-prefill of prompt + kept tokens
+
+
+def test_staleness_releases_cache_but_keeps_tokens():
+    L = _lengths(80, 7, cap=200)
+    a = _mk(L, Q=8, max_staleness=1)
+    ga = a.run_to_completion(4)
+    b = _mk(L, Q=8, max_staleness=-1)
+    b.run_to_completion(4)
+    assert a.n_stale > 0 and b.n_stale == 0
+    assert a.discarded_tokens == 0 and a.gen_tokens == int(L.sum())
+    assert a.prefill_tokens > b.prefill_tokens
+    assert a.step_no >= b.step_no
+    assert sorted(s.seq_id for g in ga for s in g) == list(range(80))
+    # a cache never outlives max_staleness + 1 versions at a boundary
+    c = _mk(L, Q=8, max_staleness=1)
+    while c.queue or any(x is not None for x in c.slots):
+        c.step()
+        if len(c.finished) >= 4:
+            c.harvest(4)
+            assert all(c.version - s.kv_version <= 1 for s in c.slots if s is not None)
+
+
+def test_on_policy_mode_discards_unfinished_tokens_at_each_boundary():
+    L = _lengths(48, 8, cap=150)
+    o = _mk(L, Q=8, mode=MODE_ONPOLICY)
+    groups = o.run_to_completion(4)
+    assert sorted(s.seq_id for g in groups for s in g) == list(range(48))
+    assert [s.gen_len for s in o.seqs] == list(L)
+    st = o.stats()
+    assert st["discarded_tokens"] > 0
+    assert st["gen_tokens"] == int(L.sum()) + st["discarded_tokens"]
+
+
+def test_micro_curriculum_completion_steps_non_decreasing_across_groups():
+    L = _lengths(256, 9)
+    o = _mk(L, Q=32)
+    groups = o.run_to_completion(16)
+    last = [max(s.completion_step for s in g) for g in groups]
+    first = [min(s.completion_step for s in g) for g in groups]
+    assert all(last[i] <= first[i + 1] for i in range(len(groups) - 1))
+    means = [np.mean([s.gen_len for s in g]) for g in groups]
+    assert means[-1] > means[0]                                    # the last group is the long tail
+
+
+def test_splitmix64_permutation_is_a_permutation_and_matches_published_first_outputs():
+    p = splitmix64_permutation(1000, 42)
+    assert sorted(p) == list(range(1000)) and p != list(range(1000))
+    # first three splitmix64 outputs for seed 1234567 as listed with the reference C code
+    import oracle.scheduler as S
+    st, outs = 1234567, []
+    for _ in range(3):
+        st = (st + 0x9E3779B97F4A7C15) & S._M64
+        z = st
+        z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & S._M64
+        z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & S._M64
+        outs.append(z ^ (z >> 31))
+    assert outs == [6457827717110365317, 3203168211198807973, 9817491932198370423]
+    assert splitmix64_permutation(5, 7) == splitmix64_permutation(5, 7)
+
+
+def test_natural_eos_and_model_driven_rollout_tiny():
+    """With a real model: greedy tokens equal a fresh full-prefix recompute of each finished trajectory."""
+    m = W.ModelShape(1, 16, 2, 2, 8, 32, 12, 1e-5, 1e4, 0)
+    g = np.random.default_rng(3)
+    w = {n: g.standard_normal((r, c)) * 0.5 for n, r, c in W.weight_layout(m)}
+    model = OracleModel(m, w)
+    pool = PagedKV(1, 12, 4, 2, 8, np.float64)
+    o = OracleRollout(max_slots=2, page_tokens=4, n_pages=12, max_new_tokens=9, eos_id=11,
+                      eos_mode=EOS_NATURAL_OR_FORCED, model=model, kv_pool=pool, page_seed=5)
+    prompts = [g.integers(0, 11, 3).astype(np.int32) for _ in range(5)]
+    o.submit(prompts, [0, 4, 0, 6, 0])
+    groups = o.run_to_completion(2)
+    assert sorted(s.seq_id for gr in groups for s in gr) == list(range(5))
+    for s in o.seqs:
+        assert 1 <= s.gen_len <= 9
+        for t in range(s.gen_len):
+            forced = s.target_len > 0 and t + 1 == s.target_len
+            lg = model.full_recompute(s.prompt + s.tokens[:t])
+            assert s.tokens[t] == (11 if forced else int(np.argmax(lg)))
+            assert abs(np.exp(s.logp[t]) - np.exp(lg[s.tokens[t]] - lg.max()) / np.exp(lg - lg.max()).sum()) < 1e-9
+        last = s.tokens[-1]
+        assert last == 11 or s.gen_len == 9
+        assert 11 not in s.tokens[:-1]
+
+
+def test_full_size_configs_run_and_report_bubbles():
+    c = W.CONFIGS["8b"]
+    L = W.make_target_lengths(c.n_prompts, c.len_mu, c.len_sigma, c.cap, c.seed_lengths)
+    res = {}
+    for mode in (MODE_PARTIAL, MODE_SYNC):
+        o = OracleRollout(max_slots=c.max_slots, page_tokens=16, n_pages=70_000, max_new_tokens=c.cap,
+                          eos_id=c.model.eos_id, mode=mode)
+        o.submit([np.zeros(c.prompt_len, np.int32)] * c.n_prompts, L)
+        groups = o.run_to_completion(c.harvest)
+        assert sum(len(g) for g in groups) == c.n_prompts
+        res[mode] = o.bubble_ratio()
+    closed = 1 - L.sum() / (c.max_slots * sum(int(L[b:b + c.max_slots].max())
+                                               for b in range(0, c.n_prompts, c.max_slots)))
+    assert abs(res[MODE_SYNC] - closed) < 1e-12
+    assert res[MODE_PARTIAL] < res[MODE_SYNC]
