@@ -1,0 +1,205 @@
+/*
+ * librollout -- the rollout phase of length-aware (SortedRL-style) RL training on one MI355X.
+ *
+ * The four core calls follow the paper's statement of the problem (Fig. 2 steps 1-4, Sec. 3.1-3.3):
+ * a controller feeds more prompts than the engine has running slots (oversubscription), the engine
+ * decodes one token per running request per step, finished short rollouts leave the batch early and
+ * are handed back in length-ordered update groups, freed slots are refilled from the queue, and
+ * unfinished rollouts stay cached across update boundaries (partial mode).
+ *
+ * Conventions
+ *   - Plain C ABI.  Every call returns 0 (ROLLOUT_OK) or a negative ROLLOUT_E* code;
+ *     rollout_last_error() gives a library-owned message valid until the next call on that ctx.
+ *   - Pointers are HOST pointers unless the name ends in _dev (device memory on cfg.device).
+ *   - The library copies what it is given; the caller keeps ownership of every buffer it passes
+ *     in and of every output buffer it provides.  One ctx is used from one thread at a time.
+ *   - Everything runs in hand-written HIP kernels on the ctx's own stream; there is no CPU
+ *     fallback: without a usable GPU rollout_init fails with ROLLOUT_EDEVICE.
+ */
+#ifndef ROLLOUT_H
+#define ROLLOUT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rollout_ctx rollout_ctx; /* opaque */
+
+enum {
+  ROLLOUT_OK = 0,
+  ROLLOUT_EINVAL = -1,  /* bad argument / unsupported configuration */
+  ROLLOUT_ENOMEM = -2,  /* KV pool cannot hold one maximum-length rollout, or allocation failed */
+  ROLLOUT_EBUSY = -3,   /* grouped-loading gate closed, or sequence table full */
+  ROLLOUT_ERANGE = -4,  /* prompt too long, token id out of range, output buffer too small */
+  ROLLOUT_EDEVICE = -5  /* HIP error; the ctx is unusable afterwards */
+};
+
+enum { ROLLOUT_EOS_FORCED_ONLY = 0, ROLLOUT_EOS_NATURAL_OR_FORCED = 1 };
+/* Sec. 3.2: partial mode keeps unfinished rollouts (tokens, log-probs, KV) across update boundaries;
+ * on-policy mode terminates them at a boundary and re-queues their prompts; SYNC is the canonical
+ * baseline the paper compares against (a batch is admitted only when every slot is empty). */
+enum { ROLLOUT_MODE_PARTIAL = 0, ROLLOUT_MODE_ONPOLICY = 1, ROLLOUT_MODE_SYNC = 2 };
+enum { ROLLOUT_FLUSH = 1 };
+enum {
+  ROLLOUT_DEBUG_NO_MODEL = 1,   /* scheduler kernels only: every non-forced token is 0 */
+  ROLLOUT_DEBUG_TIME_ATTN = 2   /* bracket each decode-attention launch with HIP events (see rollout_stats) */
+};
+
+typedef struct rollout_cfg {
+  /* policy shape (pre-norm decoder, GQA, rotate-half RoPE, SwiGLU, untied LM head) */
+  uint32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  float rms_eps, rope_theta;
+  uint32_t qkv_bias;          /* 0/1 */
+  uint32_t weight_dtype;      /* element type of the weights blob: 0 = fp32 (rounded to bf16 at init), 1 = bf16 */
+  uint32_t weights_on_device; /* 0 = `weights` is a host pointer, 1 = device pointer */
+  /* engine */
+  uint32_t max_slots;         /* Q: running-queue size (Sec. 4.4.1) */
+  uint32_t page_tokens;       /* must be 16 */
+  uint64_t kv_pool_bytes;     /* 0 = size the pool for max_slots maximum-length rollouts */
+  uint32_t max_prompt_len, max_new_tokens;
+  uint32_t max_seqs;          /* capacity of the sequence table = most submitted-but-unharvested rollouts */
+  int32_t eos_id;
+  uint32_t eos_mode;          /* ROLLOUT_EOS_* */
+  uint32_t mode;              /* ROLLOUT_MODE_* */
+  int32_t max_staleness;      /* update boundaries a KV cache may survive; -1 = unlimited */
+  uint32_t grouped_loading;   /* 1 = rollout_submit refused until the previous group is fully harvested (Sec. 3.1) */
+  uint32_t debug_flags;       /* ROLLOUT_DEBUG_* */
+  uint64_t page_seed;         /* seeds the initial order of the page free list */
+  int32_t device;             /* HIP device ordinal */
+  uint32_t reserved;
+} rollout_cfg;
+
+typedef struct rollout_step_info {
+  uint64_t step;                   /* index of the step just executed */
+  uint32_t n_ran;                  /* r_s: slots that produced a token this step (prefill or decode) */
+  uint32_t n_active;               /* running requests after the step */
+  uint32_t n_finished_unharvested;
+  uint32_t n_queued;
+  uint32_t free_pages;
+  uint32_t n_admitted;             /* admitted (prefilled) this step */
+  uint32_t n_finished_step;
+  uint32_t n_preempted_step;
+} rollout_step_info;
+
+typedef struct rollout_traj {
+  uint64_t seq_id;           /* submission order, 0-based */
+  uint32_t slot;             /* slot of the (last) admission */
+  uint32_t completion_step;
+  uint32_t gen_len;
+  uint32_t group_idx;        /* running index of the update group this record belongs to */
+  uint64_t tok_off;          /* offset of its gen_len tokens (and log-probs) in tok_buf / logp_buf */
+  uint32_t n_preempt;
+  uint32_t reserved;
+} rollout_traj;
+
+typedef struct rollout_stats_t {
+  uint64_t steps;
+  uint64_t busy;             /* sum_s r_s */
+  uint64_t idle;             /* sum_s (Q - r_s): numerator of eq. 4 with dt = 1 step */
+  uint64_t steps_q, idle_q;  /* the same restricted to steps that began with a non-empty queue */
+  uint64_t gen_tokens, discarded_tokens, prefill_tokens;
+  uint64_t n_preempt, n_stale, version;
+  uint64_t n_pages, max_pages_used;
+  /* filled when ROLLOUT_DEBUG_TIME_ATTN is set: decode-attention launches of decode rows only */
+  uint64_t attn_launches;
+  uint64_t attn_kv_tokens;   /* sum over those launches of the cached tokens attended (all kv heads share it) */
+  double attn_ms;            /* summed HIP-event time of those launches */
+  double wall_ms_steps;      /* host wall time spent inside rollout_step */
+} rollout_stats_t;
+
+/* Fig. 2 / Sec. 3.3: build the engine.  `weights` holds, in this order,
+ *   embed[V,D], per layer { attn_norm[D], wq[Hq*d,D], wk[Hkv*d,D], wv[Hkv*d,D], (bq,bk,bv if qkv_bias),
+ *   wo[D,Hq*d], ffn_norm[D], w_gate[F,D], w_up[F,D], w_down[D,F] }, final_norm[D], lm_head[V,D],
+ * every matrix row-major [out, in].  The blob is copied (and repacked) before the call returns.
+ * Errors: EINVAL (null / unsupported shape: head_dim must be 32 or 128, Hq/Hkv in {1,4,5}, page_tokens 16,
+ * max_slots <= 1024, d_model, d_ffn multiples of 64), ENOMEM, EDEVICE. */
+int rollout_init(rollout_ctx** out, const void* weights, size_t weights_bytes, const rollout_cfg* cfg);
+
+/* Fig. 2 step 1 "feed prompts": append n prompts to the FIFO queue.  tokens = concatenated ids,
+ * offsets[n+1] delimits them, target_len[i] > 0 forces EOS as the target_len-th generated token
+ * (Sec. 4.4.1 pins per-sample lengths this way), 0 = no forced length.  first_seq_id (nullable) receives the id
+ * of the first prompt; ids are consecutive.  Nothing is consumed on error.
+ * Errors: ERANGE (empty or over-long prompt, id outside [0, vocab), target_len > max_new_tokens),
+ * EBUSY (grouped loading: previous group not fully harvested; or more than max_seqs unharvested). */
+int rollout_submit(rollout_ctx*, const int32_t* tokens, const uint32_t* offsets, const uint32_t* target_len,
+                   uint32_t n, uint64_t* first_seq_id);
+
+/* One global decode step (Sec. 3.1): refill free slots from the queue head (prefill), decode one token for
+ * every other running request, emit (forced EOS / greedy argmax, lowest index on ties), evict finished
+ * rollouts and free their pages, grow pages (preempting the shortest rollout if the pool is empty).
+ * info is nullable. */
+int rollout_step(rollout_ctx*, rollout_step_info* info);
+
+/* Fig. 2 steps 3-4 "collect" and "sort and feed training batches": cut the finished-unharvested rollouts,
+ * sorted by (completion_step, gen_len, seq_id), into complete groups of group_size; with ROLLOUT_FLUSH and
+ * nothing queued or running the remainder forms a last short group.  recs[0..n_recs) are in that order;
+ * tokens (and log-probs when logp_buf != NULL) are packed at recs[i].tok_off.  Each returned group is one
+ * update boundary (policy version += 1); caches older than max_staleness are then released for re-prefill
+ * (partial mode) or unfinished rollouts are discarded and re-queued (on-policy mode).
+ * If recs_cap or tok_cap is too small: ERANGE, n_recs / tok_needed report the sizes, nothing is consumed. */
+int rollout_harvest(rollout_ctx*, uint32_t group_size, uint32_t flags, rollout_traj* recs, uint32_t recs_cap,
+                    int32_t* tok_buf, float* logp_buf, uint64_t tok_cap, uint32_t* n_groups, uint32_t* n_recs,
+                    uint64_t* tok_needed);
+
+/* Eq. 4 counters and friends. */
+int rollout_stats(rollout_ctx*, rollout_stats_t* out);
+
+/* Teacher forcing for parity tests: like rollout_step, but slot i emits forced_tok[i] when it is >= 0
+ * (forced_tok has max_slots entries), and logits_out (nullable, host, max_slots * vocab floats) receives
+ * the fp32 logits row of every slot that ran (other rows are left untouched). */
+int rollout_step_forced(rollout_ctx*, const int32_t* forced_tok, float* logits_out, rollout_step_info* info);
+
+/* Sec. 4.1 "incomplete request state retrieval": copy out the partial trajectory of any sequence.
+ * state: 0 queued, 1 active, 2 finished, 3 harvested.  tok_buf/logp_buf nullable; cap in elements. */
+int rollout_peek(rollout_ctx*, uint64_t seq_id, int32_t* tok_buf, float* logp_buf, uint32_t cap,
+                 uint32_t* gen_len, uint32_t* state, int32_t* slot);
+
+/* Debug: page ids currently held by a slot (n = 0 if the slot is empty). */
+int rollout_slot_pages(rollout_ctx*, uint32_t slot, int32_t* pages, uint32_t cap, uint32_t* n);
+
+const char* rollout_last_error(rollout_ctx*);
+void rollout_destroy(rollout_ctx*);
+
+/* ---- the ragged paged GQA decode-attention kernel alone (Sec. 2.2: rollout is bound by streaming KV caches) ----
+ * KV pool layout (bf16): for page p and kv head g, a block of 2 * 16 * head_dim elements at
+ *   ((p * n_kv_heads + g) * 2 * 16 * head_dim):  K as [head_dim/8][16 tokens][8 dims], then
+ *   V as [2 token-halves][head_dim][8 tokens].
+ * All pointers are device pointers; `stream` is a hipStream_t (NULL = default stream). */
+
+/* Bytes of a pool of n_pages pages (one layer). */
+uint64_t rollout_attn_pool_bytes(uint32_t n_pages, uint32_t n_kv_heads, uint32_t head_dim);
+
+/* Scatter n_tok rows of k, v (bf16 [n_tok, Hkv, d]) into the pool: row t belongs to sequence tok_seq_dev[t]
+ * at position tok_pos_dev[t]; page_table_dev is int32 [n_seqs, max_pages]. */
+int rollout_attn_write_kv(void* pool_dev, uint32_t n_kv_heads, uint32_t head_dim, const void* k_dev,
+                          const void* v_dev, const int32_t* tok_seq_dev, const int32_t* tok_pos_dev,
+                          const int32_t* page_table_dev, uint32_t max_pages, uint64_t n_tok, void* stream);
+
+/* Workspace bytes rollout_attn_plan / rollout_attn_decode need for n sequences whose lengths sum to total_ctx. */
+uint64_t rollout_attn_workspace_bytes(uint32_t n, uint64_t total_ctx, uint32_t n_q_heads, uint32_t head_dim);
+
+/* Build the (sequence, 256-token chunk) work list for context lengths ctx_len (host int32 [n], each >= 1) at the
+ * head of workspace_dev.  Synchronous (blocking host-to-device copies).  n_work receives the item count. */
+int rollout_attn_plan(const int32_t* ctx_len, uint32_t n, uint32_t n_q_heads, uint32_t head_dim,
+                      void* workspace_dev, uint64_t workspace_bytes, uint32_t* n_work);
+
+/* o[i] = softmax(q[i] K_i^T / sqrt(d)) V_i for the n planned sequences: q_dev bf16 [n, Hq, d]; out_dev fp32
+ * [n, Hq, d] if out_fp32 else bf16.  Only enqueues kernels on `stream`; never synchronises or allocates.
+ * Errors: EINVAL (null pointer, unsupported head_dim / group size). */
+int rollout_attn_decode(const void* pool_dev, uint32_t n_q_heads, uint32_t n_kv_heads, uint32_t head_dim,
+                        const void* q_dev, const int32_t* page_table_dev, uint32_t max_pages, uint32_t n,
+                        uint32_t n_work, void* out_dev, int out_fp32, void* workspace_dev, void* stream);
+
+/* ---- the bf16 MFMA projection GEMM alone: c[M,N] (fp32) = a[M,K] (bf16) * w[N,K]^T (bf16) ----
+ * K must be a multiple of 64.  workspace_dev needs rollout_gemm_workspace_bytes(M, N, K) bytes. */
+uint64_t rollout_gemm_workspace_bytes(uint32_t M, uint32_t N, uint32_t K);
+int rollout_gemm_bf16(const void* a_dev, const void* w_dev, float* c_dev, uint32_t M, uint32_t N, uint32_t K,
+                      void* workspace_dev, uint64_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ROLLOUT_H */

@@ -1,0 +1,275 @@
+// Ragged paged GQA decode attention for gfx950 (the KV-streaming half of the rollout step; the paper,
+// Sec. 2.2, names KV-cache loading as what bounds autoregressive rollout).
+//
+// One wavefront owns one work item = (row, kv head, chunk of ATTN_CHUNK cached tokens).  A row is one
+// query token of one slot; all G query heads that share the kv head are computed from a single pass
+// over the K/V bytes.  The page layout makes both phases stream 16-byte vectors that are contiguous
+// across lanes with no LDS staging of K or V:
+//   K block [d/8][16 tokens][8 dims]  -> score phase, one lane per token (16 lanes cover one page)
+//   V block [2][d][8 tokens]          -> value phase, one lane per output dim, tokens paired for dot2
+// Scores and values use v_dot2c_f32_bf16 with the query held in scalar registers; probabilities go
+// through a 512-byte per-wave LDS tile (bf16) to be re-read as broadcast operands.  Softmax statistics
+// and accumulators are fp32.  Chunks of one row are merged by k_attn_merge (log-sum-exp merge).
+#include "common.h"
+#include "kernels.h"
+
+#define NEG_BIG (-1.0e30f)
+
+template <int D, int G>
+__global__ __launch_bounds__(256) void k_decode_attn(
+    const uint8_t* __restrict__ pool, const uint16_t* __restrict__ q, const int* __restrict__ row_slot,
+    const int* __restrict__ row_pos, const int* __restrict__ page_table, int max_pages,
+    const int2* __restrict__ work, int Hkv, float* __restrict__ part_acc, float* __restrict__ part_ml,
+    void* __restrict__ out, int out_fp32, float scale_log2e) {
+  constexpr int NCH = D / 8;
+  constexpr int DPL = (D + 63) / 64;
+  constexpr int KBYTES = PAGE_TOKENS * D * 2;
+  constexpr int BLK = 2 * KBYTES;
+  __shared__ __align__(16) uint16_t p_lds[4][G][64];
+
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int kvh = blockIdx.y * 4 + w;
+  if (kvh >= Hkv) return;                       // whole wave leaves; no block-wide barrier below
+  const int2 it = work[blockIdx.x];
+  const int row = it.x, chunk = it.y;
+  const int slot = row_slot[row];
+  const int ctx = row_pos[row] + 1;
+  const int tok0 = chunk * ATTN_CHUNK;
+  const int tok_end = min(ctx, tok0 + ATTN_CHUNK);
+  const int last_page = (ctx - 1) >> 4;
+  const int* __restrict__ pt = page_table + (size_t)slot * max_pages;
+  const int Hq = Hkv * G;
+  const uint32_t* __restrict__ qp = (const uint32_t*)(q + ((size_t)row * Hq + (size_t)kvh * G) * D);
+
+  float m[G], l[G], acc[G][DPL];
+#pragma unroll
+  for (int h = 0; h < G; ++h) {
+    m[h] = NEG_BIG;
+    l[h] = 0.f;
+#pragma unroll
+    for (int dd = 0; dd < DPL; ++dd) acc[h][dd] = 0.f;
+  }
+
+  for (int t0 = tok0; t0 < tok_end; t0 += 64) {
+    // ---- scores: lane = token -----------------------------------------------------------------
+    const int tok = t0 + lane;
+    const int pg = pt[min(tok >> 4, last_page)];
+    const uint8_t* kb = pool + ((size_t)pg * Hkv + kvh) * BLK + (tok & 15) * 16;
+    uint4 kr[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) kr[c] = *(const uint4*)(kb + c * 256);
+    const bool valid = tok < tok_end;
+    float p[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      float s = 0.f;
+#pragma unroll
+      for (int c = 0; c < NCH; ++c) {
+        const uint32_t* qq = qp + h * (D / 2) + c * 4;
+        s = dot2_bf16(kr[c].x, qq[0], s);
+        s = dot2_bf16(kr[c].y, qq[1], s);
+        s = dot2_bf16(kr[c].z, qq[2], s);
+        s = dot2_bf16(kr[c].w, qq[3], s);
+      }
+      s = valid ? s * scale_log2e : NEG_BIG;
+      const float m_new = fmaxf(m[h], wave_max(s));
+      const float alpha = __builtin_amdgcn_exp2f(m[h] - m_new);
+      p[h] = valid ? __builtin_amdgcn_exp2f(s - m_new) : 0.f;
+      l[h] = l[h] * alpha + p[h];
+      m[h] = m_new;
+#pragma unroll
+      for (int dd = 0; dd < DPL; ++dd) acc[h][dd] *= alpha;
+      p_lds[w][h][lane] = f2bf(p[h]);
+    }
+    // ---- values: lane = output dim, operands = (token pair) x (probability pair) ---------------
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int tj = t0 + j * 16;
+      if (tj >= tok_end) break;                 // wave-uniform
+      const int pgj = __shfl(pg, j * 16, 64);
+      const uint8_t* vb = pool + ((size_t)pgj * Hkv + kvh) * BLK + KBYTES;
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        const int tb = tj + half * 8;
+        if (tb >= tok_end) break;               // wave-uniform
+        uint4 pw[G];
+#pragma unroll
+        for (int h = 0; h < G; ++h) pw[h] = *(const uint4*)&p_lds[w][h][j * 16 + half * 8];
+#pragma unroll
+        for (int dd = 0; dd < DPL; ++dd) {
+          const int dim = lane + dd * 64;
+          if (D >= 64 || dim < D) {
+            uint4 v = *(const uint4*)(vb + ((size_t)half * D + dim) * 16);
+            if (tb + 8 > tok_end) {             // ragged tail: bytes past the context may hold anything
+              const int nv = tok_end - tb;      // 1..7 valid tokens
+              uint32_t* vw = (uint32_t*)&v;
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                const uint32_t keep = (2 * i < nv ? 0x0000FFFFu : 0u) | (2 * i + 1 < nv ? 0xFFFF0000u : 0u);
+                vw[i] &= keep;
+              }
+            }
+#pragma unroll
+            for (int h = 0; h < G; ++h) {
+              float a = acc[h][dd];
+              a = dot2_bf16(v.x, pw[h].x, a);
+              a = dot2_bf16(v.y, pw[h].y, a);
+              a = dot2_bf16(v.z, pw[h].z, a);
+              a = dot2_bf16(v.w, pw[h].w, a);
+              acc[h][dd] = a;
+            }
+          }
+        }
+      }
+    }
+  }
+
+  const int nchunks = (ctx + ATTN_CHUNK - 1) / ATTN_CHUNK;
+#pragma unroll
+  for (int h = 0; h < G; ++h) {
+    const float lsum = wave_sum(l[h]);
+    const int head = kvh * G + h;
+    if (nchunks == 1) {
+      const float inv = 1.f / lsum;
+#pragma unroll
+      for (int dd = 0; dd < DPL; ++dd) {
+        const int dim = lane + dd * 64;
+        if (D >= 64 || dim < D) {
+          const size_t o = ((size_t)row * Hq + head) * D + dim;
+          if (out_fp32) ((float*)out)[o] = acc[h][dd] * inv;
+          else ((uint16_t*)out)[o] = f2bf(acc[h][dd] * inv);
+        }
+      }
+    } else {
+      const size_t pi = (size_t)blockIdx.x * Hq + head;
+#pragma unroll
+      for (int dd = 0; dd < DPL; ++dd) {
+        const int dim = lane + dd * 64;
+        if (D >= 64 || dim < D) part_acc[pi * D + dim] = acc[h][dd];
+      }
+      if (lane == 0) {
+        part_ml[pi * 2] = m[h];
+        part_ml[pi * 2 + 1] = lsum;
+      }
+    }
+  }
+}
+
+// Merge the chunk partials of one (row, query head): out = sum_c 2^(m_c - m*) acc_c / sum_c 2^(m_c - m*) l_c.
+template <int D>
+__global__ void k_attn_merge(const int* __restrict__ row_pos, const int* __restrict__ row_wstart, int Hq,
+                             const float* __restrict__ part_acc, const float* __restrict__ part_ml,
+                             void* __restrict__ out, int out_fp32) {
+  const int row = blockIdx.x, head = blockIdx.y, dim = threadIdx.x;
+  const int ctx = row_pos[row] + 1;
+  const int n = (ctx + ATTN_CHUNK - 1) / ATTN_CHUNK;
+  if (n == 1) return;
+  const int ws = row_wstart[row];
+  float mx = NEG_BIG;
+  for (int c = 0; c < n; ++c) mx = fmaxf(mx, part_ml[((size_t)(ws + c) * Hq + head) * 2]);
+  float num = 0.f, den = 0.f;
+  for (int c = 0; c < n; ++c) {
+    const size_t pi = (size_t)(ws + c) * Hq + head;
+    const float wgt = __builtin_amdgcn_exp2f(part_ml[pi * 2] - mx);
+    den += wgt * part_ml[pi * 2 + 1];
+    num += wgt * part_acc[pi * D + dim];
+  }
+  const size_t o = ((size_t)row * Hq + head) * D + dim;
+  if (out_fp32) ((float*)out)[o] = num / den;
+  else ((uint16_t*)out)[o] = f2bf(num / den);
+}
+
+// Build the (row, chunk) work list for n_rows rows on the device: one block, any n_rows.
+__global__ __launch_bounds__(1024) void k_attn_worklist(const int* __restrict__ row_pos, int n_rows,
+                                                        int2* __restrict__ work, int* __restrict__ row_wstart,
+                                                        int* __restrict__ n_work_out) {
+  __shared__ int scan[1024];
+  __shared__ int base;
+  if (threadIdx.x == 0) base = 0;
+  __syncthreads();
+  for (int r0 = 0; r0 < n_rows; r0 += 1024) {
+    const int r = r0 + threadIdx.x;
+    const int nch = r < n_rows ? (row_pos[r] + 1 + ATTN_CHUNK - 1) / ATTN_CHUNK : 0;
+    scan[threadIdx.x] = nch;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+      const int v = threadIdx.x >= o ? scan[threadIdx.x - o] : 0;
+      __syncthreads();
+      scan[threadIdx.x] += v;
+      __syncthreads();
+    }
+    const int start = base + scan[threadIdx.x] - nch;
+    if (r < n_rows) {
+      row_wstart[r] = start;
+      for (int c = 0; c < nch; ++c) work[start + c] = make_int2(r, c);
+    }
+    __syncthreads();
+    if (threadIdx.x == 1023) base += scan[1023];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0 && n_work_out) *n_work_out = base;
+}
+
+template <int D>
+__global__ void k_write_kv(uint8_t* __restrict__ pool, int Hkv, const uint16_t* __restrict__ k,
+                           const uint16_t* __restrict__ v, const int* __restrict__ tok_seq,
+                           const int* __restrict__ tok_pos, const int* __restrict__ page_table, int max_pages,
+                           size_t n_tok) {
+  constexpr int KBYTES = PAGE_TOKENS * D * 2;
+  const size_t total = n_tok * Hkv * D;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    const int dim = (int)(i % D);
+    const int kvh = (int)((i / D) % Hkv);
+    const size_t t = i / ((size_t)D * Hkv);
+    const int pos = tok_pos[t];
+    const int pg = page_table[(size_t)tok_seq[t] * max_pages + (pos >> 4)];
+    const int tk = pos & 15;
+    uint16_t* blk = (uint16_t*)(pool + ((size_t)pg * Hkv + kvh) * 2 * KBYTES);
+    blk[((dim >> 3) * 16 + tk) * 8 + (dim & 7)] = k[i];
+    blk[KBYTES / 2 + ((size_t)(tk >> 3) * D + dim) * 8 + (tk & 7)] = v[i];
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------
+int attn_supported(int head_dim, int group) {
+  return (head_dim == 128 && (group == 1 || group == 4 || group == 5)) || (head_dim == 32 && (group == 1 || group == 4));
+}
+
+void launch_attn_worklist(const int* row_pos, int n_rows, int2* work, int* row_wstart, int* n_work_out,
+                          hipStream_t st) {
+  hipLaunchKernelGGL(k_attn_worklist, dim3(1), dim3(1024), 0, st, row_pos, n_rows, work, row_wstart, n_work_out);
+}
+
+template <int D, int G>
+static void launch_attn_t(const AttnArgs& a, hipStream_t st) {
+  const float scale = 1.4426950408889634f / sqrtf((float)D);
+  dim3 grid(a.n_work, (a.Hkv + 3) / 4);
+  hipLaunchKernelGGL((k_decode_attn<D, G>), grid, dim3(256), 0, st, (const uint8_t*)a.pool, (const uint16_t*)a.q,
+                     a.row_slot, a.row_pos, a.page_table, a.max_pages, a.work, a.Hkv, a.part_acc, a.part_ml, a.out,
+                     a.out_fp32, scale);
+  if (a.need_merge)
+    hipLaunchKernelGGL((k_attn_merge<D>), dim3(a.n_rows, a.Hkv * G), dim3(D), 0, st, a.row_pos, a.row_wstart,
+                       a.Hkv * G, a.part_acc, a.part_ml, a.out, a.out_fp32);
+}
+
+void launch_decode_attn(const AttnArgs& a, int head_dim, int group, hipStream_t st) {
+  if (a.n_work <= 0) return;
+  if (head_dim == 128 && group == 4) launch_attn_t<128, 4>(a, st);
+  else if (head_dim == 128 && group == 5) launch_attn_t<128, 5>(a, st);
+  else if (head_dim == 128 && group == 1) launch_attn_t<128, 1>(a, st);
+  else if (head_dim == 32 && group == 1) launch_attn_t<32, 1>(a, st);
+  else if (head_dim == 32 && group == 4) launch_attn_t<32, 4>(a, st);
+}
+
+void launch_write_kv(void* pool, int Hkv, int head_dim, const void* k, const void* v, const int* tok_seq,
+                     const int* tok_pos, const int* page_table, int max_pages, size_t n_tok, hipStream_t st) {
+  if (n_tok == 0) return;
+  const size_t total = n_tok * Hkv * head_dim;
+  const int blocks = (int)((total + 255) / 256 < 65535 * 8 ? (total + 255) / 256 : 65535 * 8);
+  if (head_dim == 128)
+    hipLaunchKernelGGL((k_write_kv<128>), dim3(blocks), dim3(256), 0, st, (uint8_t*)pool, Hkv, (const uint16_t*)k,
+                       (const uint16_t*)v, tok_seq, tok_pos, page_table, max_pages, n_tok);
+  else
+    hipLaunchKernelGGL((k_write_kv<32>), dim3(blocks), dim3(256), 0, st, (uint8_t*)pool, Hkv, (const uint16_t*)k,
+                       (const uint16_t*)v, tok_seq, tok_pos, page_table, max_pages, n_tok);
+}

@@ -1,0 +1,222 @@
+// The small fused kernels around the projections: embedding gather, residual-add + RMSNorm (+ bf16 cast),
+// RoPE + KV page write, SiLU*mul, arg-max / log-sum-exp over the vocabulary, row gather.
+// All of them are HBM-trivial next to the weight and KV streams; each one also folds in the fixed-order
+// sum over the split-K partials of the projection that feeds it.
+#include "common.h"
+#include "kernels.h"
+
+__global__ __launch_bounds__(256) void k_embed(const uint16_t* __restrict__ table, const int* __restrict__ row_tok,
+                                               float* __restrict__ h, int D) {
+  const int r = blockIdx.x;
+  const uint16_t* src = table + (size_t)row_tok[r] * D;
+  for (int i = threadIdx.x; i < D; i += 256) h[(size_t)r * D + i] = bf2f(src[i]);
+}
+
+__device__ __forceinline__ float block_sum_256(float v, float* sh) {
+  v = wave_sum(v);
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  const float t = sh[0] + sh[1] + sh[2] + sh[3];
+  __syncthreads();
+  return t;
+}
+
+// h[r] += sum_s part[s][r] (S may be 0), then x[r] = bf16( h[r] * rsqrt(mean(h[r]^2) + eps) * gain ).
+__global__ __launch_bounds__(256) void k_add_rmsnorm(float* __restrict__ h, const float* __restrict__ part, int S,
+                                                     size_t part_stride, const float* __restrict__ gain, float eps,
+                                                     uint16_t* __restrict__ x, int D) {
+  __shared__ float sh[4];
+  const int r = blockIdx.x;
+  float v[32];
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < 32; ++i) {
+    const int c = threadIdx.x + i * 256;
+    if (c < D) {
+      float t = h[(size_t)r * D + c];
+      for (int s = 0; s < S; ++s) t += part[(size_t)s * part_stride + (size_t)r * D + c];
+      v[i] = t;
+      ss += t * t;
+    }
+  }
+  const float tot = block_sum_256(ss, sh);
+  const float inv = 1.0f / sqrtf(tot / (float)D + eps);
+#pragma unroll
+  for (int i = 0; i < 32; ++i) {
+    const int c = threadIdx.x + i * 256;
+    if (c < D) {
+      if (S > 0) h[(size_t)r * D + c] = v[i];
+      x[(size_t)r * D + c] = f2bf(v[i] * inv * gain[c]);
+    }
+  }
+}
+
+// qkv[r] = sum_s part[s][r] (+ bias); rotate-half RoPE on q and k heads at row_pos[r]; q -> bf16 [R][Hq][d];
+// k, v -> the slot's KV page (K as [d/8][16][8], V as [2][d][8]).
+__global__ __launch_bounds__(256) void k_rope_kvwrite(const float* __restrict__ part, int S, size_t part_stride,
+                                                      const float* __restrict__ bias, const int* __restrict__ row_slot,
+                                                      const int* __restrict__ row_pos, const float2* __restrict__ cs_table,
+                                                      uint16_t* __restrict__ q_out, uint8_t* __restrict__ pool,
+                                                      const int* __restrict__ page_table, int max_pages, int Hq, int Hkv,
+                                                      int d) {
+  const int r = blockIdx.x;
+  const int pos = row_pos[r];
+  const int slot = row_slot[r];
+  const int Nqkv = (Hq + 2 * Hkv) * d;
+  const int half = d / 2;
+  const float* src = part + (size_t)r * Nqkv;
+  const int pg = page_table[(size_t)slot * max_pages + (pos >> 4)];
+  const int tk = pos & 15;
+  const size_t kbytes = (size_t)PAGE_TOKENS * d * 2;
+  const int n_rot = (Hq + Hkv) * half;
+  for (int e = threadIdx.x; e < n_rot; e += 256) {
+    const int head = e / half, i = e % half;
+    const int c1 = head * d + i, c2 = c1 + half;
+    float x1 = 0.f, x2 = 0.f;
+    for (int s = 0; s < S; ++s) {
+      x1 += src[(size_t)s * part_stride + c1];
+      x2 += src[(size_t)s * part_stride + c2];
+    }
+    if (bias) {
+      x1 += bias[c1];
+      x2 += bias[c2];
+    }
+    const float2 cs = cs_table[(size_t)pos * half + i];
+    const float y1 = x1 * cs.x - x2 * cs.y;
+    const float y2 = x2 * cs.x + x1 * cs.y;
+    if (head < Hq) {
+      uint16_t* qo = q_out + ((size_t)r * Hq + head) * d;
+      qo[i] = f2bf(y1);
+      qo[i + half] = f2bf(y2);
+    } else {
+      const int kvh = head - Hq;
+      uint16_t* blk = (uint16_t*)(pool + ((size_t)pg * Hkv + kvh) * 2 * kbytes);
+      const int d1 = i, d2 = i + half;
+      blk[((d1 >> 3) * 16 + tk) * 8 + (d1 & 7)] = f2bf(y1);
+      blk[((d2 >> 3) * 16 + tk) * 8 + (d2 & 7)] = f2bf(y2);
+    }
+  }
+  const int n_v = Hkv * d;
+  const int voff = (Hq + Hkv) * d;
+  for (int e = threadIdx.x; e < n_v; e += 256) {
+    const int kvh = e / d, dim = e % d;
+    float x = 0.f;
+    for (int s = 0; s < S; ++s) x += src[(size_t)s * part_stride + voff + e];
+    if (bias) x += bias[voff + e];
+    uint16_t* blk = (uint16_t*)(pool + ((size_t)pg * Hkv + kvh) * 2 * kbytes);
+    blk[kbytes / 2 + ((size_t)(tk >> 3) * d + dim) * 8 + (tk & 7)] = f2bf(x);
+  }
+}
+
+// act[r][32*b + i] = silu(g) * u with g = sum_s part[s][r][64*b + i], u = sum_s part[s][r][64*b + 32 + i]
+// (gate and up rows are interleaved in blocks of 32 in the fused weight).
+__global__ __launch_bounds__(256) void k_silu_mul(const float* __restrict__ part, int S, size_t part_stride,
+                                                  uint16_t* __restrict__ act, int F) {
+  const int r = blockIdx.y;
+  const int f = blockIdx.x * 256 + threadIdx.x;
+  if (f >= F) return;
+  const size_t c = (size_t)r * 2 * F + (size_t)(f >> 5) * 64 + (f & 31);
+  float g = 0.f, u = 0.f;
+  for (int s = 0; s < S; ++s) {
+    g += part[(size_t)s * part_stride + c];
+    u += part[(size_t)s * part_stride + c + 32];
+  }
+  act[(size_t)r * F + f] = f2bf(g / (1.0f + __expf(-g)) * u);
+}
+
+// Per row of fp32 logits: arg-max (lowest index on ties) and log-sum-exp.
+__global__ __launch_bounds__(1024) void k_argmax_lse(const float* __restrict__ logits, int V, int* __restrict__ row_argmax,
+                                                     float* __restrict__ row_lse) {
+  __shared__ float s_val[16];
+  __shared__ int s_idx[16];
+  __shared__ float s_sum[16];
+  const float* x = logits + (size_t)blockIdx.x * V;
+  float best = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int i = threadIdx.x; i < V; i += 1024) {
+    const float v = x[i];
+    if (v > best) { best = v; bi = i; }       // strided ascending: first hit is the lowest index per thread
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float ov = __shfl_xor(best, o, 64);
+    const int oi = __shfl_xor(bi, o, 64);
+    if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+  }
+  const int w = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) { s_val[w] = best; s_idx[w] = bi; }
+  __syncthreads();
+  best = s_val[0]; bi = s_idx[0];
+  for (int k = 1; k < 16; ++k)
+    if (s_val[k] > best || (s_val[k] == best && s_idx[k] < bi)) { best = s_val[k]; bi = s_idx[k]; }
+  float sum = 0.f;
+  for (int i = threadIdx.x; i < V; i += 1024) sum += __expf(x[i] - best);
+  sum = wave_sum(sum);
+  if ((threadIdx.x & 63) == 0) s_sum[w] = sum;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float t = 0.f;
+    for (int k = 0; k < 16; ++k) t += s_sum[k];
+    row_argmax[blockIdx.x] = bi;
+    row_lse[blockIdx.x] = best + __logf(t);
+  }
+}
+
+__global__ __launch_bounds__(256) void k_gather_rows(const float* __restrict__ src, const int* __restrict__ src_row,
+                                                     float* __restrict__ dst, int dst_row0, int D) {
+  const float* s = src + (size_t)src_row[blockIdx.x] * D;
+  float* t = dst + (size_t)(dst_row0 + blockIdx.x) * D;
+  for (int i = threadIdx.x; i < D; i += 256) t[i] = s[i];
+}
+
+// Weight repacking at init: dst[row0 + (r / blk) * blk_stride + r % blk][c] = convert(src[r][c]).
+__global__ __launch_bounds__(256) void k_repack(const void* __restrict__ src, int src_fp32, void* __restrict__ dst,
+                                                int dst_fp32, size_t rows, size_t cols, size_t row0, size_t blk,
+                                                size_t blk_stride) {
+  const size_t total = rows * cols;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+    const size_t r = i / cols, c = i % cols;
+    const size_t o = (row0 + (r / blk) * blk_stride + r % blk) * cols + c;
+    if (dst_fp32) {
+      ((float*)dst)[o] = src_fp32 ? ((const float*)src)[i] : bf2f(((const uint16_t*)src)[i]);
+    } else {
+      ((uint16_t*)dst)[o] = src_fp32 ? f2bf(((const float*)src)[i]) : ((const uint16_t*)src)[i];
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------
+void launch_repack(const void* src, int src_fp32, void* dst, int dst_fp32, size_t rows, size_t cols, size_t row0,
+                   size_t blk, size_t blk_stride, hipStream_t st) {
+  const size_t total = rows * cols;
+  if (total == 0) return;
+  const size_t want = (total + 255) / 256;
+  const unsigned blocks = (unsigned)(want < 262144 ? want : 262144);
+  hipLaunchKernelGGL(k_repack, dim3(blocks), dim3(256), 0, st, src, src_fp32, dst, dst_fp32, rows, cols, row0, blk,
+                     blk_stride);
+}
+void launch_embed(const void* table, const int* row_tok, float* h, int R, int D, hipStream_t st) {
+  if (R > 0) hipLaunchKernelGGL(k_embed, dim3(R), dim3(256), 0, st, (const uint16_t*)table, row_tok, h, D);
+}
+void launch_add_rmsnorm(float* h, const float* part, int S, size_t part_stride, const float* gain, float eps, void* x,
+                        int R, int D, hipStream_t st) {
+  if (R > 0)
+    hipLaunchKernelGGL(k_add_rmsnorm, dim3(R), dim3(256), 0, st, h, part, S, part_stride, gain, eps, (uint16_t*)x, D);
+}
+void launch_rope_kvwrite(const float* part, int S, size_t part_stride, const float* bias, const int* row_slot,
+                         const int* row_pos, const void* cs_table, void* q_out, void* pool, const int* page_table,
+                         int max_pages, int Hq, int Hkv, int d, int R, hipStream_t st) {
+  if (R > 0)
+    hipLaunchKernelGGL(k_rope_kvwrite, dim3(R), dim3(256), 0, st, part, S, part_stride, bias, row_slot, row_pos,
+                       (const float2*)cs_table, (uint16_t*)q_out, (uint8_t*)pool, page_table, max_pages, Hq, Hkv, d);
+}
+void launch_silu_mul(const float* part, int S, size_t part_stride, void* act, int R, int F, hipStream_t st) {
+  if (R > 0)
+    hipLaunchKernelGGL(k_silu_mul, dim3((F + 255) / 256, R), dim3(256), 0, st, part, S, part_stride, (uint16_t*)act, F);
+}
+void launch_argmax_lse(const float* logits, int V, int* row_argmax, float* row_lse, int R, hipStream_t st) {
+  if (R > 0) hipLaunchKernelGGL(k_argmax_lse, dim3(R), dim3(1024), 0, st, logits, V, row_argmax, row_lse);
+}
+void launch_gather_rows(const float* src, const int* src_row, float* dst, int dst_row0, int n, int D, hipStream_t st) {
+  if (n > 0) hipLaunchKernelGGL(k_gather_rows, dim3(n), dim3(256), 0, st, src, src_row, dst, dst_row0, D);
+}

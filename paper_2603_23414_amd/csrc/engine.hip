@@ -1,0 +1,934 @@
+// Host engine and C ABI of librollout: owns the weights, the paged KV pool, the device-resident scheduler
+// state, and sequences the per-step kernel chain.  The host never computes any part of the method; it
+// launches kernels, reads back the small status block the scheduler kernels publish, and copies
+// trajectories out at harvest.
+#include <algorithm>
+#include <chrono>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include "../../include/rollout.h"
+#include "common.h"
+#include "kernels.h"
+
+#define PF_ROWS 4096          // token rows per prefill pass
+#define PF_MAX_WORK 32768     // attention work items per prefill pass
+
+namespace {
+
+struct LayerW {
+  float* attn_norm = nullptr;
+  uint16_t* wqkv = nullptr;
+  float* bqkv = nullptr;
+  uint16_t* wo = nullptr;
+  float* ffn_norm = nullptr;
+  uint16_t* wgu = nullptr;
+  uint16_t* wdown = nullptr;
+};
+
+struct SeqHost {
+  uint64_t seq_id = 0;
+  int prompt_len = 0;
+  bool in_use = false;
+  bool harvested = false;
+};
+
+}  // namespace
+
+struct rollout_ctx {
+  rollout_cfg cfg;
+  std::string err;
+  bool dead = false;
+  hipStream_t stream = nullptr;
+  int NL, D, Hq, Hkv, d, F, V, G, Nqkv, Q;
+  // weights
+  uint16_t* embed = nullptr;
+  uint16_t* lm_head = nullptr;
+  float* final_norm = nullptr;
+  std::vector<LayerW> layers;
+  // KV
+  uint8_t* kv_pool = nullptr;
+  size_t layer_pool_bytes = 0;
+  int n_pages = 0, max_pages = 0;
+  float2* cs_table = nullptr;
+  // scheduler
+  SchedDev sd;
+  int* status_host = nullptr;  // pinned
+  int status_ints = 0;
+  int* forced_tok_dev = nullptr;
+  // activations
+  int rows_cap = 0;
+  float* h = nullptr;
+  uint16_t* x = nullptr;
+  float* part = nullptr;
+  uint16_t* qbuf = nullptr;
+  uint16_t* attn_out = nullptr;
+  uint16_t* act = nullptr;
+  float* h_final = nullptr;
+  uint16_t* x_final = nullptr;
+  float* logits = nullptr;
+  int* row_argmax = nullptr;
+  float* row_lse = nullptr;
+  int* iota = nullptr;
+  // prefill rows + attention workspace
+  int *pf_row_slot = nullptr, *pf_row_pos = nullptr, *pf_row_tok = nullptr, *pf_row_wstart = nullptr;
+  int2* pf_work = nullptr;
+  int* pf_last_rows = nullptr;
+  PrefillDesc* pf_desc_dev = nullptr;
+  PrefillDesc* pf_desc_host = nullptr;  // pinned
+  int* pf_last_host = nullptr;          // pinned
+  float* part_acc = nullptr;
+  float* part_ml = nullptr;
+  size_t max_work = 0;
+  // submit staging (pinned + device)
+  SubmitRec* sub_host = nullptr;
+  SubmitRec* sub_dev = nullptr;
+  int* tok_stage_host = nullptr;
+  int* tok_stage_dev = nullptr;
+  // host bookkeeping
+  std::vector<SeqHost> seqs;
+  std::vector<int> free_sidx;
+  std::unordered_map<uint64_t, int> id2sidx;
+  uint64_t next_seq_id = 0, n_submitted = 0, n_harvested = 0, n_groups_total = 0;
+  // timing
+  std::vector<hipEvent_t> ev;
+  uint64_t attn_launches = 0, attn_kv_tokens = 0;
+  double attn_ms = 0.0, wall_ms_steps = 0.0;
+  std::vector<void*> allocs;
+  std::vector<void*> host_allocs;
+};
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(rollout_ctx* c, int code, const std::string& msg) {
+  if (c) c->err = msg;
+  g_err = msg;
+  return code;
+}
+
+#define HIPCHK(c, expr)                                                                              \
+  do {                                                                                               \
+    hipError_t e_ = (expr);                                                                          \
+    if (e_ != hipSuccess) {                                                                          \
+      if (c) (c)->dead = true;                                                                       \
+      return fail(c, ROLLOUT_EDEVICE, std::string(#expr) + ": " + hipGetErrorString(e_));            \
+    }                                                                                                \
+  } while (0)
+
+template <typename T>
+int dev_alloc(rollout_ctx* c, T** p, size_t n) {
+  void* q = nullptr;
+  hipError_t e = hipMalloc(&q, n * sizeof(T) + 256);
+  if (e != hipSuccess) return fail(c, ROLLOUT_ENOMEM, std::string("hipMalloc failed: ") + hipGetErrorString(e));
+  c->allocs.push_back(q);
+  *p = (T*)q;
+  return 0;
+}
+template <typename T>
+int host_alloc(rollout_ctx* c, T** p, size_t n) {
+  void* q = nullptr;
+  hipError_t e = hipHostMalloc(&q, n * sizeof(T) + 64, hipHostMallocDefault);
+  if (e != hipSuccess) return fail(c, ROLLOUT_ENOMEM, std::string("hipHostMalloc failed: ") + hipGetErrorString(e));
+  c->host_allocs.push_back(q);
+  *p = (T*)q;
+  return 0;
+}
+#define TRY(expr)          \
+  do {                     \
+    int r_ = (expr);       \
+    if (r_ != 0) return r_; \
+  } while (0)
+
+// splitmix64 (Steele, Lea, Flood 2014) driving a Fisher-Yates shuffle: initial order of the page free list
+std::vector<int> page_permutation(int n, uint64_t seed) {
+  std::vector<int> p(n);
+  for (int i = 0; i < n; ++i) p[i] = i;
+  uint64_t s = seed;
+  for (int i = n - 1; i > 0; --i) {
+    s += 0x9E3779B97F4A7C15ull;
+    uint64_t z = s;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    std::swap(p[i], p[(int)(z % (uint64_t)(i + 1))]);
+  }
+  return p;
+}
+
+int sync_status(rollout_ctx* c) {
+  HIPCHK(c, hipMemcpyAsync(c->status_host, c->sd.status, sizeof(int) * c->status_ints, hipMemcpyDeviceToHost, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  return 0;
+}
+
+// ---- weights ---------------------------------------------------------------------------------------
+struct BlobReader {
+  rollout_ctx* c;
+  const uint8_t* base;
+  size_t esz, off = 0, total;
+  void* tmp = nullptr;  // device staging for host blobs
+  size_t tmp_bytes = 0;
+  int take(size_t rows, size_t cols, void* dst, int dst_fp32, size_t row0, size_t blk, size_t blk_stride) {
+    const size_t bytes = rows * cols * esz;
+    if (off + bytes > total) return fail(c, ROLLOUT_EINVAL, "weights blob smaller than the configured shape");
+    const void* src = base + off;
+    if (!c->cfg.weights_on_device) {
+      HIPCHK(c, hipMemcpyAsync(tmp, src, bytes, hipMemcpyHostToDevice, c->stream));
+      src = tmp;
+    }
+    launch_repack(src, c->cfg.weight_dtype == 0, dst, dst_fp32, rows, cols, row0, blk ? blk : rows, blk_stride, c->stream);
+    if (!c->cfg.weights_on_device) HIPCHK(c, hipStreamSynchronize(c->stream));
+    off += bytes;
+    return 0;
+  }
+};
+
+int load_weights(rollout_ctx* c, const void* weights, size_t weights_bytes) {
+  const size_t D = c->D, F = c->F, V = c->V, qd = (size_t)c->Hq * c->d, kvd = (size_t)c->Hkv * c->d;
+  BlobReader br{c, (const uint8_t*)weights, c->cfg.weight_dtype == 0 ? (size_t)4 : (size_t)2, 0, weights_bytes};
+  if (!c->cfg.weights_on_device) {
+    br.tmp_bytes = std::max(V * D, F * D) * br.esz;
+    TRY(dev_alloc(c, (uint8_t**)&br.tmp, br.tmp_bytes));
+  }
+  TRY(dev_alloc(c, &c->embed, V * D));
+  TRY(dev_alloc(c, &c->lm_head, V * D));
+  TRY(dev_alloc(c, &c->final_norm, D));
+  TRY(br.take(V, D, c->embed, 0, 0, 0, 0));
+  c->layers.resize(c->NL);
+  for (int l = 0; l < c->NL; ++l) {
+    LayerW& L = c->layers[l];
+    TRY(dev_alloc(c, &L.attn_norm, D));
+    TRY(dev_alloc(c, &L.wqkv, (size_t)c->Nqkv * D));
+    TRY(dev_alloc(c, &L.wo, D * qd));
+    TRY(dev_alloc(c, &L.ffn_norm, D));
+    TRY(dev_alloc(c, &L.wgu, 2 * F * D));
+    TRY(dev_alloc(c, &L.wdown, D * F));
+    TRY(br.take(1, D, L.attn_norm, 1, 0, 0, 0));
+    TRY(br.take(qd, D, L.wqkv, 0, 0, 0, 0));
+    TRY(br.take(kvd, D, L.wqkv, 0, qd, 0, 0));
+    TRY(br.take(kvd, D, L.wqkv, 0, qd + kvd, 0, 0));
+    if (c->cfg.qkv_bias) {
+      TRY(dev_alloc(c, &L.bqkv, (size_t)c->Nqkv));
+      // biases are [1, n] rows in the blob: load them as n rows of one column so they land contiguously
+      TRY(br.take(qd, 1, L.bqkv, 1, 0, 0, 0));
+      TRY(br.take(kvd, 1, L.bqkv, 1, qd, 0, 0));
+      TRY(br.take(kvd, 1, L.bqkv, 1, qd + kvd, 0, 0));
+    }
+    TRY(br.take(D, qd, L.wo, 0, 0, 0, 0));
+    TRY(br.take(1, D, L.ffn_norm, 1, 0, 0, 0));
+    TRY(br.take(F, D, L.wgu, 0, 0, 32, 64));    // gate rows -> blocks 0,2,4,.. of 32
+    TRY(br.take(F, D, L.wgu, 0, 32, 32, 64));   // up rows   -> blocks 1,3,5,..
+    TRY(br.take(D, F, L.wdown, 0, 0, 0, 0));
+  }
+  TRY(br.take(1, D, c->final_norm, 1, 0, 0, 0));
+  TRY(br.take(V, D, c->lm_head, 0, 0, 0, 0));
+  if (br.off != weights_bytes) return fail(c, ROLLOUT_EINVAL, "weights blob larger than the configured shape");
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  return 0;
+}
+
+// ---- the per-step kernel chain over a set of rows (decode rows or one prefill pass) ---------------------
+void run_layers(rollout_ctx* c, int R, const int* row_slot, const int* row_pos, const int* row_tok, const int2* work,
+                const int* row_wstart, int n_work, bool time_attn) {
+  hipStream_t st = c->stream;
+  const int D = c->D, F = c->F, Hq = c->Hq, Hkv = c->Hkv, d = c->d, Nqkv = c->Nqkv;
+  const float eps = c->cfg.rms_eps;
+  launch_embed(c->embed, row_tok, c->h, R, D, st);
+  launch_add_rmsnorm(c->h, nullptr, 0, 0, c->layers[0].attn_norm, eps, c->x, R, D, st);
+  const int S1 = gemm_pick_splits(R, Nqkv, D), S2 = gemm_pick_splits(R, D, Hq * d), S3 = gemm_pick_splits(R, 2 * F, D),
+            S4 = gemm_pick_splits(R, D, F);
+  for (int l = 0; l < c->NL; ++l) {
+    const LayerW& L = c->layers[l];
+    uint8_t* pool_l = c->kv_pool + (size_t)l * c->layer_pool_bytes;
+    launch_gemm(c->x, L.wqkv, c->part, R, Nqkv, D, S1, st);
+    launch_rope_kvwrite(c->part, S1, (size_t)R * Nqkv, L.bqkv, row_slot, row_pos, c->cs_table, c->qbuf, pool_l,
+                        c->sd.page_table, c->max_pages, Hq, Hkv, d, R, st);
+    AttnArgs a;
+    a.pool = pool_l;
+    a.q = c->qbuf;
+    a.row_slot = row_slot;
+    a.row_pos = row_pos;
+    a.page_table = c->sd.page_table;
+    a.max_pages = c->max_pages;
+    a.work = work;
+    a.row_wstart = row_wstart;
+    a.n_work = n_work;
+    a.n_rows = R;
+    a.Hkv = Hkv;
+    a.part_acc = c->part_acc;
+    a.part_ml = c->part_ml;
+    a.out = c->attn_out;
+    a.out_fp32 = 0;
+    a.need_merge = n_work > R;
+    if (time_attn) (void)hipEventRecord(c->ev[2 * l], st);
+    launch_decode_attn(a, d, c->G, st);
+    if (time_attn) (void)hipEventRecord(c->ev[2 * l + 1], st);
+    launch_gemm(c->attn_out, L.wo, c->part, R, D, Hq * d, S2, st);
+    launch_add_rmsnorm(c->h, c->part, S2, (size_t)R * D, L.ffn_norm, eps, c->x, R, D, st);
+    launch_gemm(c->x, L.wgu, c->part, R, 2 * F, D, S3, st);
+    launch_silu_mul(c->part, S3, (size_t)R * 2 * F, c->act, R, F, st);
+    launch_gemm(c->act, L.wdown, c->part, R, D, F, S4, st);
+    const float* next_gain = l + 1 < c->NL ? c->layers[l + 1].attn_norm : c->final_norm;
+    launch_add_rmsnorm(c->h, c->part, S4, (size_t)R * D, next_gain, eps, c->x, R, D, st);
+  }
+}
+
+// attention work items of positions [p0, p1) of one sequence
+inline long long work_items(int p0, int p1) {
+  long long s = 0;
+  for (int p = p0; p < p1; ++p) s += (p + 1 + ATTN_CHUNK - 1) / ATTN_CHUNK;
+  return s;
+}
+
+int run_prefill(rollout_ctx* c, int n_dec, int n_adm) {
+  // admitted sequences in ascending slot order: (slot, sidx, n_tok) triples in the status block
+  const int* desc = c->status_host + STAT_HDR;
+  int a = 0, pos = 0;  // cursor: sequence a, next position pos
+  while (a < n_adm) {
+    int rows = 0, n_desc = 0, n_last = 0;
+    long long items = 0;
+    while (a < n_adm && rows < PF_ROWS) {
+      const int slot = desc[3 * a], sidx = desc[3 * a + 1], n = desc[3 * a + 2];
+      int take = std::min(n - pos, PF_ROWS - rows);
+      // shrink the piece until its attention work fits the pass
+      long long w = work_items(pos, pos + take);
+      while (take > 1 && items + w > PF_MAX_WORK) {
+        take = std::max(1, take / 2);
+        w = work_items(pos, pos + take);
+      }
+      if (items + w > PF_MAX_WORK && rows > 0) break;
+      c->pf_desc_host[n_desc++] = PrefillDesc{slot, sidx, take, pos, rows};
+      rows += take;
+      items += w;
+      pos += take;
+      if (pos == n) {
+        c->pf_last_host[2 * n_last] = rows - 1;   // row holding the sequence's last token
+        c->pf_last_host[2 * n_last + 1] = a;      // its index among the admitted
+        ++n_last;
+        ++a;
+        pos = 0;
+      }
+      if (items >= PF_MAX_WORK) break;
+    }
+    hipStream_t st = c->stream;
+    HIPCHK(c, hipMemcpyAsync(c->pf_desc_dev, c->pf_desc_host, sizeof(PrefillDesc) * n_desc, hipMemcpyHostToDevice, st));
+    launch_prefill_rows(c->sd, c->pf_desc_dev, n_desc, c->pf_row_slot, c->pf_row_pos, c->pf_row_tok, st);
+    launch_attn_worklist(c->pf_row_pos, rows, c->pf_work, c->pf_row_wstart, nullptr, st);
+    run_layers(c, rows, c->pf_row_slot, c->pf_row_pos, c->pf_row_tok, c->pf_work, c->pf_row_wstart, (int)items, false);
+    for (int j = 0; j < n_last; ++j) {
+      // one tiny gather per finished prompt: h row -> h_final row n_dec + (index among admitted)
+      const int src_row = c->pf_last_host[2 * j], dst = n_dec + c->pf_last_host[2 * j + 1];
+      launch_gather_rows(c->h, c->iota + src_row, c->h_final, dst, 1, c->D, st);
+    }
+    // the pinned descriptor buffer is reused by the next pass
+    HIPCHK(c, hipStreamSynchronize(st));
+  }
+  return 0;
+}
+
+int step_impl(rollout_ctx* c, const int32_t* forced_tok, float* logits_out, rollout_step_info* info) {
+  if (!c) return ROLLOUT_EINVAL;
+  if (c->dead) return fail(c, ROLLOUT_EDEVICE, "context unusable after an earlier device error");
+  const auto t0 = std::chrono::steady_clock::now();
+  HIPCHK(c, hipSetDevice(c->cfg.device));
+  hipStream_t st = c->stream;
+  int* sh = c->status_host;
+  const int Q = c->Q;
+  const int n_dec = sh[STAT_NDEC_NEXT], n_work = sh[STAT_NWORK_NEXT];
+  const unsigned long long ctx_sum = (unsigned long long)(unsigned)sh[STAT_CTX_LO] | ((unsigned long long)(unsigned)sh[STAT_CTX_HI] << 32);
+  const int n_active = sh[STAT_NACTIVE];
+  int n_adm = 0;
+  const bool can_admit = sh[STAT_QUEUED] > 0 && n_active < Q && !(c->cfg.mode == ROLLOUT_MODE_SYNC && n_active > 0);
+  if (can_admit) {
+    launch_sched_admit(c->sd, st);
+    TRY(sync_status(c));
+    n_adm = sh[STAT_NADM];
+  }
+  if (forced_tok) {
+    HIPCHK(c, hipMemcpyAsync(c->forced_tok_dev, forced_tok, sizeof(int) * Q, hipMemcpyHostToDevice, st));
+    c->sd.forced_tok = c->forced_tok_dev;
+  } else {
+    c->sd.forced_tok = nullptr;
+  }
+  const bool model = !(c->cfg.debug_flags & ROLLOUT_DEBUG_NO_MODEL);
+  const bool time_attn = (c->cfg.debug_flags & ROLLOUT_DEBUG_TIME_ATTN) != 0;
+  const int n_rows = n_dec + n_adm;
+  if (model && n_rows > 0) {
+    if (n_dec > 0) {
+      run_layers(c, n_dec, c->sd.row_slot, c->sd.row_pos, c->sd.row_tok, c->sd.work, c->sd.row_wstart, n_work, time_attn);
+      launch_gather_rows(c->h, c->iota, c->h_final, 0, n_dec, c->D, st);
+    }
+    if (n_adm > 0) TRY(run_prefill(c, n_dec, n_adm));
+    launch_add_rmsnorm(c->h_final, nullptr, 0, 0, c->final_norm, c->cfg.rms_eps, c->x_final, n_rows, c->D, st);
+    launch_gemm(c->x_final, c->lm_head, c->logits, n_rows, c->V, c->D, 1, st);
+    launch_argmax_lse(c->logits, c->V, c->row_argmax, c->row_lse, n_rows, st);
+  }
+  launch_sched_emit(c->sd, st);
+  TRY(sync_status(c));
+  if (time_attn && model && n_dec > 0) {
+    for (int l = 0; l < c->NL; ++l) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, c->ev[2 * l], c->ev[2 * l + 1]) == hipSuccess) c->attn_ms += ms;
+    }
+    c->attn_launches += c->NL;
+    c->attn_kv_tokens += ctx_sum * (unsigned long long)c->NL;
+  }
+  if (info) {
+    info->step = (uint64_t)sh[STAT_STEP];
+    info->n_ran = (uint32_t)sh[STAT_R];
+    info->n_active = (uint32_t)sh[STAT_NACTIVE];
+    info->n_finished_unharvested = (uint32_t)sh[STAT_FIN];
+    info->n_queued = (uint32_t)sh[STAT_QUEUED];
+    info->free_pages = (uint32_t)sh[STAT_FREE];
+    info->n_admitted = (uint32_t)sh[STAT_NADM];
+    info->n_finished_step = (uint32_t)sh[STAT_NFIN_STEP];
+    info->n_preempted_step = (uint32_t)sh[STAT_NPRE_STEP];
+  }
+  c->wall_ms_steps += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+  (void)logits_out;
+  return 0;
+}
+
+}  // namespace
+
+// =====================================================================================================
+extern "C" {
+
+const char* rollout_last_error(rollout_ctx* c) { return c ? c->err.c_str() : g_err.c_str(); }
+
+void rollout_destroy(rollout_ctx* c) {
+  if (!c) return;
+  (void)hipSetDevice(c->cfg.device);
+  if (c->stream) (void)hipStreamSynchronize(c->stream);
+  for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
+  for (void* p : c->allocs) (void)hipFree(p);
+  for (void* p : c->host_allocs) (void)hipHostFree(p);
+  if (c->stream) (void)hipStreamDestroy(c->stream);
+  delete c;
+}
+
+int rollout_init(rollout_ctx** out, const void* weights, size_t weights_bytes, const rollout_cfg* cfg) {
+  if (!out || !cfg || !weights) return fail(nullptr, ROLLOUT_EINVAL, "null argument");
+  *out = nullptr;
+  const rollout_cfg& f = *cfg;
+  if (f.n_layers == 0 || f.d_model == 0 || f.n_q_heads == 0 || f.n_kv_heads == 0 || f.d_ffn == 0 || f.vocab == 0)
+    return fail(nullptr, ROLLOUT_EINVAL, "zero-sized model dimension");
+  if (f.n_q_heads % f.n_kv_heads != 0 || !attn_supported((int)f.head_dim, (int)(f.n_q_heads / f.n_kv_heads)))
+    return fail(nullptr, ROLLOUT_EINVAL, "unsupported head_dim / query-group size (head_dim 32 or 128, group 1, 4 or 5)");
+  if (f.page_tokens != PAGE_TOKENS) return fail(nullptr, ROLLOUT_EINVAL, "page_tokens must be 16");
+  if (f.max_slots == 0 || f.max_slots > 1024) return fail(nullptr, ROLLOUT_EINVAL, "max_slots must be in 1..1024");
+  if (f.d_model % 64 || f.d_ffn % 64 || (f.n_q_heads * f.head_dim) % 64 || f.d_model > 8192)
+    return fail(nullptr, ROLLOUT_EINVAL, "d_model, d_ffn and n_q_heads*head_dim must be multiples of 64; d_model <= 8192");
+  if (f.max_prompt_len == 0 || f.max_new_tokens == 0 || f.max_seqs == 0)
+    return fail(nullptr, ROLLOUT_EINVAL, "max_prompt_len, max_new_tokens and max_seqs must be positive");
+  if (f.eos_id < 0 || (uint32_t)f.eos_id >= f.vocab) return fail(nullptr, ROLLOUT_EINVAL, "eos_id outside the vocabulary");
+  if (f.mode > 2 || f.eos_mode > 1 || f.weight_dtype > 1) return fail(nullptr, ROLLOUT_EINVAL, "bad mode / eos_mode / weight_dtype");
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0 || f.device < 0 || f.device >= ndev)
+    return fail(nullptr, ROLLOUT_EDEVICE, "no usable HIP device (this library has no CPU fallback)");
+
+  rollout_ctx* c = new rollout_ctx();
+  c->cfg = f;
+  c->NL = f.n_layers; c->D = f.d_model; c->Hq = f.n_q_heads; c->Hkv = f.n_kv_heads; c->d = f.head_dim;
+  c->F = f.d_ffn; c->V = f.vocab; c->G = c->Hq / c->Hkv; c->Nqkv = (c->Hq + 2 * c->Hkv) * c->d; c->Q = f.max_slots;
+#define INIT_TRY(expr)        \
+  do {                        \
+    int r_ = (expr);          \
+    if (r_ != 0) {            \
+      g_err = c->err;         \
+      rollout_destroy(c);     \
+      return r_;              \
+    }                         \
+  } while (0)
+#define INIT_HIP(expr)                                                                          \
+  do {                                                                                          \
+    hipError_t e_ = (expr);                                                                     \
+    if (e_ != hipSuccess) {                                                                     \
+      g_err = std::string(#expr) + ": " + hipGetErrorString(e_);                                \
+      rollout_destroy(c);                                                                       \
+      return ROLLOUT_EDEVICE;                                                                   \
+    }                                                                                           \
+  } while (0)
+  INIT_HIP(hipSetDevice(f.device));
+  INIT_HIP(hipStreamCreateWithFlags(&c->stream, hipStreamNonBlocking));
+
+  // ---- KV pool --------------------------------------------------------------------------------------
+  c->max_pages = (int)((f.max_prompt_len + f.max_new_tokens + PAGE_TOKENS - 1) / PAGE_TOKENS);
+  const size_t page_layer_bytes = (size_t)c->Hkv * kv_block_bytes(c->d);
+  const size_t page_bytes = page_layer_bytes * c->NL;
+  long long n_pages = f.kv_pool_bytes ? (long long)(f.kv_pool_bytes / page_bytes) : (long long)c->Q * c->max_pages;
+  if (n_pages < c->max_pages) {
+    g_err = "kv_pool_bytes cannot hold one maximum-length rollout";
+    rollout_destroy(c);
+    return ROLLOUT_ENOMEM;
+  }
+  if (n_pages > (1ll << 30)) n_pages = 1ll << 30;
+  c->n_pages = (int)n_pages;
+  c->layer_pool_bytes = (size_t)c->n_pages * page_layer_bytes;
+  INIT_TRY(dev_alloc(c, &c->kv_pool, c->layer_pool_bytes * c->NL));
+  INIT_HIP(hipMemsetAsync(c->kv_pool, 0, c->layer_pool_bytes * c->NL, c->stream));
+
+  // ---- RoPE table: cos/sin of pos * theta^(-2i/d), evaluated in double --------------------------------
+  {
+    const int max_pos = (int)(f.max_prompt_len + f.max_new_tokens), half = c->d / 2;
+    std::vector<float2> tab((size_t)max_pos * half);
+    for (int i = 0; i < half; ++i) {
+      const double freq = std::pow((double)f.rope_theta, -2.0 * i / c->d);
+      for (int p = 0; p < max_pos; ++p) {
+        const double ang = (double)p * freq;
+        tab[(size_t)p * half + i] = make_float2((float)std::cos(ang), (float)std::sin(ang));
+      }
+    }
+    INIT_TRY(dev_alloc(c, &c->cs_table, tab.size()));
+    INIT_HIP(hipMemcpy(c->cs_table, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice));
+  }
+
+  // ---- scheduler state -------------------------------------------------------------------------------
+  SchedDev& s = c->sd;
+  memset(&s, 0, sizeof(s));
+  s.Q = c->Q; s.max_pages = c->max_pages; s.n_pages = c->n_pages; s.max_seqs = f.max_seqs;
+  int qcap = 1;
+  while (qcap < (int)f.max_seqs + 1) qcap <<= 1;
+  s.qmask = qcap - 1;
+  s.tok_stride = f.max_prompt_len + f.max_new_tokens; s.cap = f.max_new_tokens; s.eos_id = f.eos_id;
+  s.eos_mode = f.eos_mode; s.mode = f.mode; s.max_staleness = f.max_staleness;
+  s.no_model = (f.debug_flags & ROLLOUT_DEBUG_NO_MODEL) ? 1 : 0; s.V = c->V;
+  const size_t MS = f.max_seqs, Q = c->Q;
+  INIT_TRY(dev_alloc(c, &s.sc, SC_COUNT));
+  INIT_TRY(dev_alloc(c, &s.ctr, CT_COUNT));
+  INIT_TRY(dev_alloc(c, &s.slot_seq, Q));
+  INIT_TRY(dev_alloc(c, &s.slot_npages, Q));
+  INIT_TRY(dev_alloc(c, &s.page_table, Q * c->max_pages));
+  INIT_TRY(dev_alloc(c, &s.seq_prompt_len, MS));
+  INIT_TRY(dev_alloc(c, &s.seq_target_len, MS));
+  INIT_TRY(dev_alloc(c, &s.seq_gen_len, MS));
+  INIT_TRY(dev_alloc(c, &s.seq_state, MS));
+  INIT_TRY(dev_alloc(c, &s.seq_slot, MS));
+  INIT_TRY(dev_alloc(c, &s.seq_completion, MS));
+  INIT_TRY(dev_alloc(c, &s.seq_kv_version, MS));
+  INIT_TRY(dev_alloc(c, &s.seq_npreempt, MS));
+  INIT_TRY(dev_alloc(c, &s.seq_id, MS));
+  INIT_TRY(dev_alloc(c, &s.seq_tokens, MS * s.tok_stride));
+  INIT_TRY(dev_alloc(c, &s.seq_logp, MS * s.cap));
+  INIT_TRY(dev_alloc(c, &s.q_ring, (size_t)qcap));
+  INIT_TRY(dev_alloc(c, &s.free_stack, (size_t)c->n_pages));
+  INIT_TRY(dev_alloc(c, &s.fin_list, MS));
+  INIT_TRY(dev_alloc(c, &s.row_slot, Q));
+  INIT_TRY(dev_alloc(c, &s.row_pos, Q));
+  INIT_TRY(dev_alloc(c, &s.row_tok, Q));
+  INIT_TRY(dev_alloc(c, &s.row_wstart, Q));
+  const size_t dec_work = Q * (size_t)((s.tok_stride + ATTN_CHUNK - 1) / ATTN_CHUNK);
+  INIT_TRY(dev_alloc(c, &s.work, dec_work));
+  c->status_ints = STAT_HDR + 3 * c->Q;
+  INIT_TRY(dev_alloc(c, &s.status, (size_t)c->status_ints));
+  INIT_TRY(host_alloc(c, &c->status_host, (size_t)c->status_ints));
+  INIT_TRY(dev_alloc(c, &c->forced_tok_dev, Q));
+  INIT_HIP(hipMemsetAsync(s.seq_tokens, 0, MS * s.tok_stride * sizeof(int), c->stream));
+  {
+    std::vector<int> perm = page_permutation(c->n_pages, f.page_seed);
+    INIT_HIP(hipMemcpy(s.free_stack, perm.data(), perm.size() * sizeof(int), hipMemcpyHostToDevice));
+  }
+  launch_sched_init(s, c->stream);
+  c->seqs.resize(MS);
+  for (int i = (int)MS - 1; i >= 0; --i) c->free_sidx.push_back(i);
+  INIT_TRY(host_alloc(c, &c->sub_host, MS));
+  INIT_TRY(dev_alloc(c, &c->sub_dev, MS));
+  INIT_TRY(host_alloc(c, &c->tok_stage_host, MS * f.max_prompt_len));
+  INIT_TRY(dev_alloc(c, &c->tok_stage_dev, MS * f.max_prompt_len));
+
+  // ---- activations / workspaces ----------------------------------------------------------------------
+  const bool model = !(f.debug_flags & ROLLOUT_DEBUG_NO_MODEL);
+  if (model) {
+    const size_t R = std::max<size_t>(Q, PF_ROWS);
+    c->rows_cap = (int)R;
+    const size_t D = c->D, F = c->F, V = c->V;
+    INIT_TRY(dev_alloc(c, &c->h, R * D));
+    INIT_TRY(dev_alloc(c, &c->x, R * D));
+    size_t part_elems = 0;   // split-K partials: worst case over every row count a chain can run with
+    for (size_t rows = 1; rows <= R; ++rows) {
+      const int r = (int)rows;
+      part_elems = std::max(part_elems, (size_t)gemm_pick_splits(r, c->Nqkv, c->D) * rows * c->Nqkv);
+      part_elems = std::max(part_elems, (size_t)gemm_pick_splits(r, c->D, c->Hq * c->d) * rows * D);
+      part_elems = std::max(part_elems, (size_t)gemm_pick_splits(r, 2 * c->F, c->D) * rows * 2 * F);
+      part_elems = std::max(part_elems, (size_t)gemm_pick_splits(r, c->D, c->F) * rows * D);
+    }
+    INIT_TRY(dev_alloc(c, &c->part, part_elems));
+    INIT_TRY(dev_alloc(c, &c->qbuf, R * c->Hq * c->d));
+    INIT_TRY(dev_alloc(c, &c->attn_out, R * c->Hq * c->d));
+    INIT_TRY(dev_alloc(c, &c->act, R * F));
+    INIT_TRY(dev_alloc(c, &c->h_final, Q * D));
+    INIT_TRY(dev_alloc(c, &c->x_final, Q * D));
+    INIT_TRY(dev_alloc(c, &c->logits, Q * V));
+    INIT_TRY(dev_alloc(c, &c->row_argmax, Q));
+    INIT_TRY(dev_alloc(c, &c->row_lse, Q));
+    INIT_TRY(dev_alloc(c, &c->iota, R));
+    {
+      std::vector<int> io(R);
+      for (size_t i = 0; i < R; ++i) io[i] = (int)i;
+      INIT_HIP(hipMemcpy(c->iota, io.data(), R * sizeof(int), hipMemcpyHostToDevice));
+    }
+    INIT_TRY(dev_alloc(c, &c->pf_row_slot, (size_t)PF_ROWS));
+    INIT_TRY(dev_alloc(c, &c->pf_row_pos, (size_t)PF_ROWS));
+    INIT_TRY(dev_alloc(c, &c->pf_row_tok, (size_t)PF_ROWS));
+    INIT_TRY(dev_alloc(c, &c->pf_row_wstart, (size_t)PF_ROWS));
+    c->max_work = std::max<size_t>(dec_work, (size_t)PF_MAX_WORK + 128);
+    INIT_TRY(dev_alloc(c, &c->pf_work, c->max_work));
+    INIT_TRY(dev_alloc(c, &c->pf_desc_dev, (size_t)PF_ROWS));
+    INIT_TRY(host_alloc(c, &c->pf_desc_host, (size_t)PF_ROWS));
+    INIT_TRY(host_alloc(c, &c->pf_last_host, (size_t)2 * PF_ROWS));
+    INIT_TRY(dev_alloc(c, &c->part_acc, c->max_work * c->Hq * c->d));
+    INIT_TRY(dev_alloc(c, &c->part_ml, c->max_work * c->Hq * 2));
+    s.row_argmax = c->row_argmax;
+    s.row_lse = c->row_lse;
+    s.logits = c->logits;
+    INIT_TRY(load_weights(c, weights, weights_bytes));
+    if (f.debug_flags & ROLLOUT_DEBUG_TIME_ATTN) {
+      c->ev.resize(2 * (size_t)c->NL);
+      for (auto& e : c->ev) INIT_HIP(hipEventCreate(&e));
+    }
+  }
+  INIT_TRY(sync_status(c));
+  *out = c;
+  return ROLLOUT_OK;
+#undef INIT_TRY
+#undef INIT_HIP
+}
+
+int rollout_submit(rollout_ctx* c, const int32_t* tokens, const uint32_t* offsets, const uint32_t* target_len,
+                   uint32_t n, uint64_t* first_seq_id) {
+  if (!c || !tokens || !offsets || (!target_len && n)) return fail(c, ROLLOUT_EINVAL, "null argument");
+  if (c->dead) return fail(c, ROLLOUT_EDEVICE, "context unusable after an earlier device error");
+  if (c->cfg.grouped_loading && c->n_submitted != c->n_harvested)
+    return fail(c, ROLLOUT_EBUSY, "grouped loading: the previous group is not fully harvested");
+  if (n > c->free_sidx.size()) return fail(c, ROLLOUT_EBUSY, "sequence table full (max_seqs unharvested rollouts)");
+  for (uint32_t i = 0; i < n; ++i) {
+    if (offsets[i + 1] <= offsets[i] || offsets[i + 1] - offsets[i] > c->cfg.max_prompt_len)
+      return fail(c, ROLLOUT_ERANGE, "empty or over-long prompt");
+    if (target_len[i] > c->cfg.max_new_tokens) return fail(c, ROLLOUT_ERANGE, "target_len exceeds max_new_tokens");
+    for (uint32_t j = offsets[i]; j < offsets[i + 1]; ++j)
+      if (tokens[j] < 0 || (uint32_t)tokens[j] >= c->cfg.vocab) return fail(c, ROLLOUT_ERANGE, "token id outside the vocabulary");
+  }
+  if (first_seq_id) *first_seq_id = c->next_seq_id;
+  if (n == 0) return ROLLOUT_OK;
+  HIPCHK(c, hipSetDevice(c->cfg.device));
+  size_t tok_off = 0;
+  for (uint32_t i = 0; i < n; ++i) {
+    const int sidx = c->free_sidx.back();
+    c->free_sidx.pop_back();
+    const int plen = (int)(offsets[i + 1] - offsets[i]);
+    SeqHost& sh = c->seqs[sidx];
+    sh.seq_id = c->next_seq_id++;
+    sh.prompt_len = plen;
+    sh.in_use = true;
+    sh.harvested = false;
+    c->id2sidx[sh.seq_id] = sidx;
+    c->sub_host[i] = SubmitRec{sidx, plen, (int)target_len[i], (int)tok_off, sh.seq_id};
+    memcpy(c->tok_stage_host + tok_off, tokens + offsets[i], sizeof(int) * plen);
+    tok_off += plen;
+  }
+  c->n_submitted += n;
+  HIPCHK(c, hipMemcpyAsync(c->sub_dev, c->sub_host, sizeof(SubmitRec) * n, hipMemcpyHostToDevice, c->stream));
+  HIPCHK(c, hipMemcpyAsync(c->tok_stage_dev, c->tok_stage_host, sizeof(int) * tok_off, hipMemcpyHostToDevice, c->stream));
+  launch_sched_submit(c->sd, c->sub_dev, c->tok_stage_dev, (int)n, c->stream);
+  TRY(sync_status(c));
+  return ROLLOUT_OK;
+}
+
+int rollout_step(rollout_ctx* c, rollout_step_info* info) { return step_impl(c, nullptr, nullptr, info); }
+
+int rollout_step_forced(rollout_ctx* c, const int32_t* forced_tok, float* logits_out, rollout_step_info* info) {
+  if (!c) return ROLLOUT_EINVAL;
+  if (!logits_out) return step_impl(c, forced_tok, nullptr, info);
+  // the emit kernel rewrites the row list, so capture this step's row -> slot map before it runs:
+  // the decode rows are known before the step; admitted slots come from the status block afterwards
+  const int n_dec = c->status_host[STAT_NDEC_NEXT];
+  std::vector<int> row_slot(c->Q, -1);
+  if (n_dec > 0) {
+    HIPCHK(c, hipMemcpy(row_slot.data(), c->sd.row_slot, sizeof(int) * n_dec, hipMemcpyDeviceToHost));
+  }
+  const int r = step_impl(c, forced_tok, logits_out, info);
+  if (r != 0) return r;
+  if (c->cfg.debug_flags & ROLLOUT_DEBUG_NO_MODEL) return 0;
+  const int n_adm = c->status_host[STAT_NADM];
+  for (int a = 0; a < n_adm; ++a) row_slot[n_dec + a] = c->status_host[STAT_HDR + 3 * a];
+  for (int row = 0; row < n_dec + n_adm; ++row)
+    HIPCHK(c, hipMemcpy(logits_out + (size_t)row_slot[row] * c->V, c->logits + (size_t)row * c->V, sizeof(float) * c->V,
+                        hipMemcpyDeviceToHost));
+  return 0;
+}
+
+int rollout_harvest(rollout_ctx* c, uint32_t group_size, uint32_t flags, rollout_traj* recs, uint32_t recs_cap,
+                    int32_t* tok_buf, float* logp_buf, uint64_t tok_cap, uint32_t* n_groups, uint32_t* n_recs,
+                    uint64_t* tok_needed) {
+  if (!c || group_size == 0 || !n_groups) return fail(c, ROLLOUT_EINVAL, "null argument or zero group size");
+  if (c->dead) return fail(c, ROLLOUT_EDEVICE, "context unusable after an earlier device error");
+  HIPCHK(c, hipSetDevice(c->cfg.device));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  *n_groups = 0;
+  if (n_recs) *n_recs = 0;
+  if (tok_needed) *tok_needed = 0;
+  const int* sh = c->status_host;
+  const int nfin = sh[STAT_FIN];
+  const bool drained = sh[STAT_QUEUED] == 0 && sh[STAT_NACTIVE] == 0;
+  int k = nfin / (int)group_size;
+  int take = k * (int)group_size;
+  if ((flags & ROLLOUT_FLUSH) && drained && nfin > take) {
+    take = nfin;
+    ++k;
+  }
+  if (k == 0) return ROLLOUT_OK;
+  const size_t MS = c->cfg.max_seqs;
+  std::vector<int> fin(nfin), comp(MS), glen(MS), slot(MS), npre(MS);
+  HIPCHK(c, hipMemcpy(fin.data(), c->sd.fin_list, sizeof(int) * nfin, hipMemcpyDeviceToHost));
+  HIPCHK(c, hipMemcpy(comp.data(), c->sd.seq_completion, sizeof(int) * MS, hipMemcpyDeviceToHost));
+  HIPCHK(c, hipMemcpy(glen.data(), c->sd.seq_gen_len, sizeof(int) * MS, hipMemcpyDeviceToHost));
+  HIPCHK(c, hipMemcpy(slot.data(), c->sd.seq_slot, sizeof(int) * MS, hipMemcpyDeviceToHost));
+  HIPCHK(c, hipMemcpy(npre.data(), c->sd.seq_npreempt, sizeof(int) * MS, hipMemcpyDeviceToHost));
+  // length-ordered: completion step, then generated length, then submission order
+  std::sort(fin.begin(), fin.end(), [&](int a, int b) {
+    if (comp[a] != comp[b]) return comp[a] < comp[b];
+    if (glen[a] != glen[b]) return glen[a] < glen[b];
+    return c->seqs[a].seq_id < c->seqs[b].seq_id;
+  });
+  uint64_t need_tok = 0;
+  for (int i = 0; i < take; ++i) need_tok += (uint64_t)glen[fin[i]];
+  if (n_recs) *n_recs = (uint32_t)take;
+  if (tok_needed) *tok_needed = need_tok;
+  if (!recs || (uint32_t)take > recs_cap || !tok_buf || need_tok > tok_cap)
+    return fail(c, ROLLOUT_ERANGE, "output buffers too small (see n_recs / tok_needed); nothing consumed");
+  uint64_t off = 0;
+  for (int i = 0; i < take; ++i) {
+    const int sidx = fin[i];
+    rollout_traj& r = recs[i];
+    r.seq_id = c->seqs[sidx].seq_id;
+    r.slot = (uint32_t)slot[sidx];
+    r.completion_step = (uint32_t)comp[sidx];
+    r.gen_len = (uint32_t)glen[sidx];
+    r.group_idx = (uint32_t)(c->n_groups_total + (uint64_t)(i / (int)group_size));
+    r.tok_off = off;
+    r.n_preempt = (uint32_t)npre[sidx];
+    r.reserved = 0;
+    HIPCHK(c, hipMemcpy(tok_buf + off, c->sd.seq_tokens + (size_t)sidx * c->sd.tok_stride + c->seqs[sidx].prompt_len,
+                        sizeof(int) * glen[sidx], hipMemcpyDeviceToHost));
+    if (logp_buf)
+      HIPCHK(c, hipMemcpy(logp_buf + off, c->sd.seq_logp + (size_t)sidx * c->sd.cap, sizeof(float) * glen[sidx],
+                          hipMemcpyDeviceToHost));
+    off += glen[sidx];
+    c->seqs[sidx].harvested = true;
+    c->seqs[sidx].in_use = false;
+    c->id2sidx.erase(c->seqs[sidx].seq_id);
+    c->free_sidx.push_back(sidx);
+  }
+  // remainder stays finished-unharvested, in its sorted order
+  const int rest = nfin - take;
+  if (rest > 0) HIPCHK(c, hipMemcpy(c->sd.fin_list, fin.data() + take, sizeof(int) * rest, hipMemcpyHostToDevice));
+  HIPCHK(c, hipMemcpy(c->sd.sc + SC_FINCOUNT, &rest, sizeof(int), hipMemcpyHostToDevice));
+  c->n_harvested += take;
+  c->n_groups_total += k;
+  *n_groups = (uint32_t)k;
+  launch_sched_boundary(c->sd, k, c->stream);   // update boundary: version += k, staleness / on-policy eviction
+  TRY(sync_status(c));
+  return ROLLOUT_OK;
+}
+
+int rollout_stats(rollout_ctx* c, rollout_stats_t* out) {
+  if (!c || !out) return fail(c, ROLLOUT_EINVAL, "null argument");
+  if (c->dead) return fail(c, ROLLOUT_EDEVICE, "context unusable after an earlier device error");
+  HIPCHK(c, hipSetDevice(c->cfg.device));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  unsigned long long ctr[CT_COUNT];
+  int sc[SC_COUNT];
+  HIPCHK(c, hipMemcpy(ctr, c->sd.ctr, sizeof(ctr), hipMemcpyDeviceToHost));
+  HIPCHK(c, hipMemcpy(sc, c->sd.sc, sizeof(sc), hipMemcpyDeviceToHost));
+  memset(out, 0, sizeof(*out));
+  out->steps = (uint64_t)sc[SC_STEP];
+  out->busy = ctr[CT_BUSY];
+  out->idle = ctr[CT_IDLE];
+  out->steps_q = ctr[CT_STEPS_Q];
+  out->idle_q = ctr[CT_IDLE_Q];
+  out->gen_tokens = ctr[CT_GEN];
+  out->discarded_tokens = ctr[CT_DISCARD];
+  out->prefill_tokens = ctr[CT_PREFILL];
+  out->n_preempt = ctr[CT_PREEMPT];
+  out->n_stale = ctr[CT_STALE];
+  out->version = (uint64_t)sc[SC_VERSION];
+  out->n_pages = (uint64_t)c->n_pages;
+  out->max_pages_used = (uint64_t)(c->n_pages - sc[SC_MINFREE]);
+  out->attn_launches = c->attn_launches;
+  out->attn_kv_tokens = c->attn_kv_tokens;
+  out->attn_ms = c->attn_ms;
+  out->wall_ms_steps = c->wall_ms_steps;
+  return ROLLOUT_OK;
+}
+
+int rollout_peek(rollout_ctx* c, uint64_t seq_id, int32_t* tok_buf, float* logp_buf, uint32_t cap, uint32_t* gen_len,
+                 uint32_t* state, int32_t* slot) {
+  if (!c) return ROLLOUT_EINVAL;
+  if (c->dead) return fail(c, ROLLOUT_EDEVICE, "context unusable after an earlier device error");
+  if (seq_id >= c->next_seq_id) return fail(c, ROLLOUT_ERANGE, "unknown seq_id");
+  auto it = c->id2sidx.find(seq_id);
+  if (it == c->id2sidx.end()) {   // harvested: its table entry has been recycled
+    if (gen_len) *gen_len = 0;
+    if (state) *state = SEQ_HARVESTED;
+    if (slot) *slot = -1;
+    return ROLLOUT_OK;
+  }
+  const int sidx = it->second;
+  HIPCHK(c, hipSetDevice(c->cfg.device));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  int g = 0, stt = 0, sl = -1;
+  HIPCHK(c, hipMemcpy(&g, c->sd.seq_gen_len + sidx, sizeof(int), hipMemcpyDeviceToHost));
+  HIPCHK(c, hipMemcpy(&stt, c->sd.seq_state + sidx, sizeof(int), hipMemcpyDeviceToHost));
+  HIPCHK(c, hipMemcpy(&sl, c->sd.seq_slot + sidx, sizeof(int), hipMemcpyDeviceToHost));
+  if (gen_len) *gen_len = (uint32_t)g;
+  if (state) *state = (uint32_t)stt;
+  if (slot) *slot = stt == SEQ_ACTIVE ? sl : -1;
+  if ((tok_buf || logp_buf) && (uint32_t)g > cap) return fail(c, ROLLOUT_ERANGE, "buffer smaller than gen_len");
+  if (tok_buf && g > 0)
+    HIPCHK(c, hipMemcpy(tok_buf, c->sd.seq_tokens + (size_t)sidx * c->sd.tok_stride + c->seqs[sidx].prompt_len,
+                        sizeof(int) * g, hipMemcpyDeviceToHost));
+  if (logp_buf && g > 0)
+    HIPCHK(c, hipMemcpy(logp_buf, c->sd.seq_logp + (size_t)sidx * c->sd.cap, sizeof(float) * g, hipMemcpyDeviceToHost));
+  return ROLLOUT_OK;
+}
+
+int rollout_slot_pages(rollout_ctx* c, uint32_t slot, int32_t* pages, uint32_t cap, uint32_t* n) {
+  if (!c || !n || slot >= (uint32_t)c->Q) return fail(c, ROLLOUT_EINVAL, "bad argument");
+  if (c->dead) return fail(c, ROLLOUT_EDEVICE, "context unusable after an earlier device error");
+  HIPCHK(c, hipSetDevice(c->cfg.device));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  int sidx = -1, np = 0;
+  HIPCHK(c, hipMemcpy(&sidx, c->sd.slot_seq + slot, sizeof(int), hipMemcpyDeviceToHost));
+  HIPCHK(c, hipMemcpy(&np, c->sd.slot_npages + slot, sizeof(int), hipMemcpyDeviceToHost));
+  if (sidx < 0) np = 0;
+  *n = (uint32_t)np;
+  if (np == 0) return ROLLOUT_OK;
+  if (!pages || (uint32_t)np > cap) return fail(c, ROLLOUT_ERANGE, "buffer smaller than the page count");
+  HIPCHK(c, hipMemcpy(pages, c->sd.page_table + (size_t)slot * c->max_pages, sizeof(int) * np, hipMemcpyDeviceToHost));
+  return ROLLOUT_OK;
+}
+
+// ---- standalone attention ------------------------------------------------------------------------------
+uint64_t rollout_attn_pool_bytes(uint32_t n_pages, uint32_t n_kv_heads, uint32_t head_dim) {
+  return (uint64_t)n_pages * n_kv_heads * kv_block_bytes((int)head_dim);
+}
+
+int rollout_attn_write_kv(void* pool_dev, uint32_t n_kv_heads, uint32_t head_dim, const void* k_dev, const void* v_dev,
+                          const int32_t* tok_seq_dev, const int32_t* tok_pos_dev, const int32_t* page_table_dev,
+                          uint32_t max_pages, uint64_t n_tok, void* stream) {
+  if (!pool_dev || !k_dev || !v_dev || !tok_seq_dev || !tok_pos_dev || !page_table_dev)
+    return fail(nullptr, ROLLOUT_EINVAL, "null argument");
+  if (head_dim != 128 && head_dim != 32) return fail(nullptr, ROLLOUT_EINVAL, "head_dim must be 32 or 128");
+  launch_write_kv(pool_dev, (int)n_kv_heads, (int)head_dim, k_dev, v_dev, tok_seq_dev, tok_pos_dev, page_table_dev,
+                  (int)max_pages, (size_t)n_tok, (hipStream_t)stream);
+  return hipGetLastError() == hipSuccess ? ROLLOUT_OK : fail(nullptr, ROLLOUT_EDEVICE, "kernel launch failed");
+}
+
+static inline uint64_t align256(uint64_t x) { return (x + 255) & ~(uint64_t)255; }
+struct AttnWs { uint64_t row_slot, row_pos, row_wstart, work, part_ml, part_acc, total; };
+static AttnWs attn_ws_layout(uint32_t n, uint64_t max_work, uint32_t Hq, uint32_t d) {
+  AttnWs w;
+  uint64_t o = 0;
+  w.row_slot = o; o = align256(o + 4ull * n);
+  w.row_pos = o; o = align256(o + 4ull * n);
+  w.row_wstart = o; o = align256(o + 4ull * n);
+  w.work = o; o = align256(o + 8ull * max_work);
+  w.part_ml = o; o = align256(o + 8ull * max_work * Hq);
+  w.part_acc = o; o = align256(o + 4ull * max_work * Hq * d);
+  w.total = o;
+  return w;
+}
+uint64_t rollout_attn_workspace_bytes(uint32_t n, uint64_t total_ctx, uint32_t n_q_heads, uint32_t head_dim) {
+  const uint64_t max_work = total_ctx / ATTN_CHUNK + n;
+  return attn_ws_layout(n, max_work, n_q_heads, head_dim).total;
+}
+
+int rollout_attn_plan(const int32_t* ctx_len, uint32_t n, uint32_t n_q_heads, uint32_t head_dim, void* workspace_dev,
+                      uint64_t workspace_bytes, uint32_t* n_work) {
+  if (!ctx_len || !workspace_dev || !n_work || n == 0) return fail(nullptr, ROLLOUT_EINVAL, "null argument");
+  uint64_t total = 0;
+  for (uint32_t i = 0; i < n; ++i) {
+    if (ctx_len[i] < 1) return fail(nullptr, ROLLOUT_EINVAL, "context lengths must be >= 1");
+    total += (uint64_t)ctx_len[i];
+  }
+  const uint64_t max_work = total / ATTN_CHUNK + n;
+  const AttnWs w = attn_ws_layout(n, max_work, n_q_heads, head_dim);
+  if (w.total > workspace_bytes) return fail(nullptr, ROLLOUT_EINVAL, "workspace too small");
+  std::vector<int> rs(n), rp(n), ws(n);
+  std::vector<int2> work;
+  work.reserve(max_work);
+  for (uint32_t i = 0; i < n; ++i) {
+    rs[i] = (int)i;
+    rp[i] = ctx_len[i] - 1;
+    ws[i] = (int)work.size();
+    const int nch = (ctx_len[i] + ATTN_CHUNK - 1) / ATTN_CHUNK;
+    for (int ch = 0; ch < nch; ++ch) work.push_back(make_int2((int)i, ch));
+  }
+  uint8_t* base = (uint8_t*)workspace_dev;
+  if (hipMemcpy(base + w.row_slot, rs.data(), 4ull * n, hipMemcpyHostToDevice) != hipSuccess ||
+      hipMemcpy(base + w.row_pos, rp.data(), 4ull * n, hipMemcpyHostToDevice) != hipSuccess ||
+      hipMemcpy(base + w.row_wstart, ws.data(), 4ull * n, hipMemcpyHostToDevice) != hipSuccess ||
+      hipMemcpy(base + w.work, work.data(), 8ull * work.size(), hipMemcpyHostToDevice) != hipSuccess)
+    return fail(nullptr, ROLLOUT_EDEVICE, "hipMemcpy failed");
+  *n_work = (uint32_t)work.size();
+  return ROLLOUT_OK;
+}
+
+int rollout_attn_decode(const void* pool_dev, uint32_t n_q_heads, uint32_t n_kv_heads, uint32_t head_dim,
+                        const void* q_dev, const int32_t* page_table_dev, uint32_t max_pages, uint32_t n, uint32_t n_work,
+                        void* out_dev, int out_fp32, void* workspace_dev, void* stream) {
+  if (!pool_dev || !q_dev || !page_table_dev || !out_dev || !workspace_dev || n == 0 || n_work < n)
+    return fail(nullptr, ROLLOUT_EINVAL, "null argument");
+  if (n_kv_heads == 0 || n_q_heads % n_kv_heads || !attn_supported((int)head_dim, (int)(n_q_heads / n_kv_heads)))
+    return fail(nullptr, ROLLOUT_EINVAL, "unsupported head_dim / query-group size");
+  // row arrays and the work list sit where the plan put them (their offsets depend on n only); the partial
+  // buffers are scratch of this call and are laid out for n_work items, which never exceeds the planned bound
+  uint8_t* base = (uint8_t*)workspace_dev;
+  const AttnWs w = attn_ws_layout(n, n_work, n_q_heads, head_dim);
+  AttnArgs a;
+  a.pool = pool_dev;
+  a.q = q_dev;
+  a.row_slot = (const int*)(base + w.row_slot);
+  a.row_pos = (const int*)(base + w.row_pos);
+  a.page_table = page_table_dev;
+  a.max_pages = (int)max_pages;
+  a.work = (const int2*)(base + w.work);
+  a.row_wstart = (const int*)(base + w.row_wstart);
+  a.n_work = (int)n_work;
+  a.n_rows = (int)n;
+  a.Hkv = (int)n_kv_heads;
+  a.part_ml = (float*)(base + w.part_ml);
+  a.part_acc = (float*)(base + w.part_acc);
+  a.out = out_dev;
+  a.out_fp32 = out_fp32;
+  a.need_merge = n_work > n;
+  launch_decode_attn(a, (int)head_dim, (int)(n_q_heads / n_kv_heads), (hipStream_t)stream);
+  return hipGetLastError() == hipSuccess ? ROLLOUT_OK : fail(nullptr, ROLLOUT_EDEVICE, "kernel launch failed");
+}
+
+// ---- standalone GEMM ---------------------------------------------------------------------------------------
+uint64_t rollout_gemm_workspace_bytes(uint32_t M, uint32_t N, uint32_t K) {
+  return (uint64_t)gemm_pick_splits((int)M, (int)N, (int)K) * M * N * 4ull + 256;
+}
+int rollout_gemm_bf16(const void* a_dev, const void* w_dev, float* c_dev, uint32_t M, uint32_t N, uint32_t K,
+                      void* workspace_dev, uint64_t workspace_bytes, void* stream) {
+  if (!a_dev || !w_dev || !c_dev || M == 0 || N == 0 || K == 0) return fail(nullptr, ROLLOUT_EINVAL, "null argument");
+  if (K % 64) return fail(nullptr, ROLLOUT_EINVAL, "K must be a multiple of 64");
+  const int S = gemm_pick_splits((int)M, (int)N, (int)K);
+  if (S == 1) {
+    launch_gemm(a_dev, w_dev, c_dev, (int)M, (int)N, (int)K, 1, (hipStream_t)stream);
+  } else {
+    if (!workspace_dev || workspace_bytes < (uint64_t)S * M * N * 4ull) return fail(nullptr, ROLLOUT_EINVAL, "workspace too small");
+    launch_gemm(a_dev, w_dev, (float*)workspace_dev, (int)M, (int)N, (int)K, S, (hipStream_t)stream);
+    launch_reduce_splits((const float*)workspace_dev, c_dev, (size_t)M * N, S, (hipStream_t)stream);
+  }
+  return hipGetLastError() == hipSuccess ? ROLLOUT_OK : fail(nullptr, ROLLOUT_EDEVICE, "kernel launch failed");
+}
+
+}  // extern "C"

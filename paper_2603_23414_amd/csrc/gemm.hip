@@ -1,0 +1,141 @@
+// bf16 MFMA projection GEMM for gfx950: C[M,N] (fp32) = A[M,K] (bf16, row-major) * W[N,K]^T (bf16, row-major).
+//
+// In decode M = running slots (<= 256), so every projection is a weight stream: each weight byte is read
+// once and the MFMA work per byte is ~M flop, at or below the machine's ridge.  The kernel is built around
+// that: a workgroup owns 128 output columns and all (<= 256) rows; each of its 4 wavefronts owns 32 columns
+// and reads its W fragments straight from global memory in the v_mfma_f32_32x32x16_bf16 operand layout
+// (lane -> row n, 16 contiguous bytes along K), so no weight byte is loaded twice or staged through LDS.
+// Only the small activation tile A goes through LDS (double-buffered, rows padded to 144 bytes so the
+// 16-byte fragment reads are bank-conflict free).  Split-K over blockIdx.z writes fp32 partial sums that
+// the consumer kernels (residual+norm, RoPE, SiLU*mul) add up in a fixed order, so results are deterministic.
+#include "common.h"
+#include "kernels.h"
+
+#define GEMM_BK 64
+#define LDS_ROW 72   // bf16 elements per LDS row: 64 + 8 padding
+
+template <int MI>
+__global__ __launch_bounds__(256) void k_gemm_bf16(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
+                                                   float* __restrict__ C, int M, int N, int K, int kb_per_split) {
+  constexpr int BM = 32 * MI;
+  __shared__ __align__(16) uint16_t a_lds[2][BM * LDS_ROW];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int n_base = blockIdx.x * 128 + w * 32;
+  const int m_base = blockIdx.y * BM;
+  const int nkb_total = K / GEMM_BK;
+  const int kb0 = blockIdx.z * kb_per_split;
+  const int nkb = min(kb_per_split, nkb_total - kb0);
+  float* __restrict__ Cz = C + (size_t)blockIdx.z * M * N;
+
+  // W fragment source: row n (clamped), k offset (lane/32)*8 within each 16-wide MFMA k-step
+  const int n_lane = min(n_base + (lane & 31), N - 1);
+  const uint16_t* __restrict__ wrow = W + (size_t)n_lane * K + (size_t)kb0 * GEMM_BK + (lane >> 5) * 8;
+
+  // A tile loads: thread -> (row, 16-byte column) ; MI loads per thread per tile
+  const int a_col = tid & 7;
+  int a_row[MI];
+  const uint16_t* a_src[MI];
+#pragma unroll
+  for (int i = 0; i < MI; ++i) {
+    a_row[i] = (tid >> 3) + i * 32;
+    const int gm = min(m_base + a_row[i], M - 1);
+    a_src[i] = A + (size_t)gm * K + (size_t)kb0 * GEMM_BK + a_col * 8;
+  }
+
+  f32x16_t acc[MI];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+
+  uint4 breg[2][4];
+  uint4 areg[MI];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) breg[0][ks] = *(const uint4*)(wrow + ks * 16);
+#pragma unroll
+  for (int i = 0; i < MI; ++i) areg[i] = *(const uint4*)(a_src[i]);
+#pragma unroll
+  for (int i = 0; i < MI; ++i) *(uint4*)&a_lds[0][a_row[i] * LDS_ROW + a_col * 8] = areg[i];
+  __syncthreads();
+
+  for (int kb = 0; kb < nkb; ++kb) {
+    const int cur = kb & 1;
+    const bool more = kb + 1 < nkb;
+    if (more) {
+      const size_t ko = (size_t)(kb + 1) * GEMM_BK;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) breg[cur ^ 1][ks] = *(const uint4*)(wrow + ko + ks * 16);
+#pragma unroll
+      for (int i = 0; i < MI; ++i) areg[i] = *(const uint4*)(a_src[i] + ko);
+    }
+    const uint16_t* al = a_lds[cur] + (lane & 31) * LDS_ROW + (lane >> 5) * 8;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const bf16x8_t bf = __builtin_bit_cast(bf16x8_t, breg[cur][ks]);
+#pragma unroll
+      for (int i = 0; i < MI; ++i) {
+        const uint4 av = *(const uint4*)(al + i * 32 * LDS_ROW + ks * 16);
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av), bf, acc[i], 0, 0, 0);
+      }
+    }
+    if (more) {
+#pragma unroll
+      for (int i = 0; i < MI; ++i) *(uint4*)&a_lds[cur ^ 1][a_row[i] * LDS_ROW + a_col * 8] = areg[i];
+    }
+    __syncthreads();
+  }
+
+  // C fragment: element j of lane -> row (j/4)*8 + (lane/32)*4 + j%4, col lane%32
+  const int n_out = n_base + (lane & 31);
+  if (n_out < N) {
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int mrow = m_base + i * 32 + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
+        if (mrow < M) Cz[(size_t)mrow * N + n_out] = acc[i][j];
+      }
+  }
+}
+
+__global__ void k_reduce_splits(const float* __restrict__ part, float* __restrict__ c, size_t mn, int S) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= mn) return;
+  float s = 0.f;
+  for (int z = 0; z < S; ++z) s += part[(size_t)z * mn + i];
+  c[i] = s;
+}
+
+// Number of K splits: enough workgroups to cover the chip's 256 CUs without drowning the weight stream
+// in partial-sum traffic.
+int gemm_pick_splits(int M, int N, int K) {
+  const int mblocks = (M + 255) / 256;
+  const int tiles = ((N + 127) / 128) * mblocks;
+  const int nkb = K / GEMM_BK;
+  int S = 1;
+  if (tiles < 192) S = (256 + tiles - 1) / tiles;
+  if (S > 8) S = 8;
+  if (S > nkb / 4) S = nkb / 4 > 0 ? nkb / 4 : 1;
+  const int per = (nkb + S - 1) / S;
+  return (nkb + per - 1) / per;
+}
+
+void launch_gemm(const void* A, const void* W, float* C, int M, int N, int K, int S, hipStream_t st) {
+  if (M <= 0) return;
+  const int nkb = K / GEMM_BK;
+  const int per = (nkb + S - 1) / S;
+  const int mi = M <= 32 ? 1 : M <= 64 ? 2 : M <= 128 ? 4 : 8;
+  dim3 grid((N + 127) / 128, (M + 32 * mi - 1) / (32 * mi), S);
+  const uint16_t* a = (const uint16_t*)A;
+  const uint16_t* w = (const uint16_t*)W;
+  switch (mi) {
+    case 1: hipLaunchKernelGGL((k_gemm_bf16<1>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
+    case 2: hipLaunchKernelGGL((k_gemm_bf16<2>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
+    case 4: hipLaunchKernelGGL((k_gemm_bf16<4>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
+    default: hipLaunchKernelGGL((k_gemm_bf16<8>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
+  }
+}
+
+void launch_reduce_splits(const float* part, float* c, size_t mn, int S, hipStream_t st) {
+  hipLaunchKernelGGL(k_reduce_splits, dim3((unsigned)((mn + 255) / 256)), dim3(256), 0, st, part, c, mn, S);
+}

@@ -1,0 +1,95 @@
+// Launchers and device-state layout shared by the engine and the kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+// ---- attention --------------------------------------------------------------------------------------
+struct AttnArgs {
+  const void* pool;        // this layer's KV pool
+  const void* q;           // bf16 [n_rows][Hq][d]
+  const int* row_slot;     // page-table row of each query row
+  const int* row_pos;      // position of the query token (context = pos + 1)
+  const int* page_table;   // int32 [slots][max_pages]
+  int max_pages;
+  const int2* work;        // (row, chunk) items
+  const int* row_wstart;   // first work item of each row
+  int n_work, n_rows, Hkv;
+  float* part_acc;         // [n_work][Hq][d]
+  float* part_ml;          // [n_work][Hq][2]
+  void* out;               // [n_rows][Hq*d], bf16 or fp32
+  int out_fp32;
+  int need_merge;          // some row spans more than one chunk
+};
+int attn_supported(int head_dim, int group);
+void launch_attn_worklist(const int* row_pos, int n_rows, int2* work, int* row_wstart, int* n_work_out, hipStream_t st);
+void launch_decode_attn(const AttnArgs& a, int head_dim, int group, hipStream_t st);
+void launch_write_kv(void* pool, int Hkv, int head_dim, const void* k, const void* v, const int* tok_seq,
+                     const int* tok_pos, const int* page_table, int max_pages, size_t n_tok, hipStream_t st);
+
+// ---- GEMM ---------------------------------------------------------------------------------------------
+int gemm_pick_splits(int M, int N, int K);
+void launch_gemm(const void* A, const void* W, float* C, int M, int N, int K, int S, hipStream_t st);
+void launch_reduce_splits(const float* part, float* c, size_t mn, int S, hipStream_t st);
+
+// ---- fused small kernels ------------------------------------------------------------------------------
+void launch_embed(const void* table, const int* row_tok, float* h, int R, int D, hipStream_t st);
+void launch_add_rmsnorm(float* h, const float* part, int S, size_t part_stride, const float* gain, float eps, void* x,
+                        int R, int D, hipStream_t st);
+void launch_rope_kvwrite(const float* part, int S, size_t part_stride, const float* bias, const int* row_slot,
+                         const int* row_pos, const void* cs_table, void* q_out, void* pool, const int* page_table,
+                         int max_pages, int Hq, int Hkv, int d, int R, hipStream_t st);
+void launch_silu_mul(const float* part, int S, size_t part_stride, void* act, int R, int F, hipStream_t st);
+void launch_argmax_lse(const float* logits, int V, int* row_argmax, float* row_lse, int R, hipStream_t st);
+void launch_gather_rows(const float* src, const int* src_row, float* dst, int dst_row0, int n, int D, hipStream_t st);
+
+// ---- scheduler state (device side of the rollout state manager / stateful buffer, Sec. 3.3) ----------
+enum { SEQ_QUEUED = 0, SEQ_ACTIVE = 1, SEQ_FINISHED = 2, SEQ_HARVESTED = 3 };
+enum {  // scalar cells in SchedDev::sc
+  SC_STEP = 0, SC_VERSION, SC_NFREE, SC_QHEAD, SC_QCOUNT, SC_FINCOUNT, SC_NDEC, SC_NPRE, SC_NWORK, SC_MINFREE,
+  SC_ADMIT_RAN, SC_QNE, SC_COUNT
+};
+enum {  // 64-bit counters in SchedDev::ctr
+  CT_BUSY = 0, CT_IDLE, CT_STEPS_Q, CT_IDLE_Q, CT_GEN, CT_DISCARD, CT_PREFILL, CT_PREEMPT, CT_STALE, CT_COUNT
+};
+enum {  // int cells of the status block copied to the host after every scheduler kernel
+  STAT_STEP = 0, STAT_R, STAT_NACTIVE, STAT_FIN, STAT_QUEUED, STAT_FREE, STAT_NADM, STAT_NFIN_STEP, STAT_NPRE_STEP,
+  STAT_NDEC_NEXT, STAT_NWORK_NEXT, STAT_CTX_LO, STAT_CTX_HI, STAT_VERSION, STAT_HDR = 16
+};  // followed by max_slots admission descriptors of 3 ints: slot, sequence-table index, tokens to prefill
+
+struct SchedDev {
+  int Q, max_pages, n_pages, max_seqs, qmask, tok_stride, cap, eos_id, eos_mode, mode, max_staleness, no_model, V;
+  int* sc;
+  unsigned long long* ctr;
+  int *slot_seq, *slot_npages, *page_table;
+  int *seq_prompt_len, *seq_target_len, *seq_gen_len, *seq_state, *seq_slot, *seq_completion, *seq_kv_version,
+      *seq_npreempt;
+  unsigned long long* seq_id;
+  int* seq_tokens;
+  float* seq_logp;
+  int *q_ring, *free_stack, *fin_list;
+  int *row_slot, *row_pos, *row_tok, *row_wstart;
+  int2* work;
+  const int* row_argmax;
+  const float* row_lse;
+  const float* logits;
+  const int* forced_tok;   // nullable
+  int* status;
+};
+
+struct SubmitRec { int sidx, prompt_len, target_len, tok_off; unsigned long long seq_id; };
+
+void launch_sched_admit(const SchedDev& d, hipStream_t st);
+void launch_sched_emit(const SchedDev& d, hipStream_t st);
+void launch_sched_boundary(const SchedDev& d, int n_groups, hipStream_t st);
+void launch_sched_submit(const SchedDev& d, const SubmitRec* recs, const int* tok_staging, int n, hipStream_t st);
+void launch_sched_init(const SchedDev& d, hipStream_t st);
+
+// prefill planning: token rows of the admitted sequences
+struct PrefillDesc { int slot, sidx, n_tok, pos_begin, row_begin; };   // a run of consecutive positions of one sequence
+void launch_prefill_rows(const SchedDev& d, const PrefillDesc* descs, int n_desc, int* row_slot, int* row_pos,
+                         int* row_tok, hipStream_t st);
+
+// weight repacking at init: dst[dst_row(r)][c] = convert(src[r][c]), dst_row(r) = row0 + (r / blk) * blk_stride + r % blk
+void launch_repack(const void* src, int src_fp32, void* dst, int dst_fp32, size_t rows, size_t cols, size_t row0,
+                   size_t blk, size_t blk_stride, hipStream_t st);

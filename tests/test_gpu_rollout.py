@@ -1,0 +1,209 @@
+"""End-to-end parity of the HIP rollout engine (through the C ABI) against the CPU oracle."""
+import numpy as np
+import pytest
+
+import workloads as W
+from tests._util import flat_prompts, info_tuple, make_engine, make_oracle
+
+pytestmark = pytest.mark.gpu
+
+
+def _harvest_both(R, ctx, orc, G, flush=False):
+    ng, recs, toks, logp = R.rollout_harvest(ctx, G, R.ROLLOUT_FLUSH if flush else 0)
+    groups = orc.harvest(G, flush=flush)
+    assert ng == len(groups)
+    flat = [s for g in groups for s in g]
+    assert len(recs) == len(flat)
+    for r, s in zip(recs, flat):
+        assert (r.seq_id, r.slot, r.completion_step, r.gen_len, r.group_idx, r.n_preempt) == \
+               (s.seq_id, s.last_slot, s.completion_step, s.gen_len, s.group_idx, s.n_preempt)
+    return recs, toks, logp, flat
+
+
+def _compare_stats(R, ctx, orc):
+    st, so = R.rollout_stats(ctx), orc.stats()
+    for k in ("steps", "busy", "idle", "steps_q", "idle_q", "gen_tokens", "discarded_tokens", "prefill_tokens",
+              "n_preempt", "n_stale", "version", "max_pages_used"):
+        assert getattr(st, k) == so[k], k
+
+
+def _scheduler_only(L, *, Q, P, cap, G, kv_pool_pages=0, max_staleness=-1, mode=0, page_seed=0, harvest_every=True):
+    """NO_MODEL run of the device scheduler against the integer oracle, step by step."""
+    import paper_2603_23414_amd as R
+    shape = W.ModelShape(1, 64, 1, 1, 32, 64, 64, 1e-5, 1e4, 0)
+    page_bytes = shape.n_layers * shape.n_kv_heads * 2 * 16 * shape.head_dim * 2
+    kvb = kv_pool_pages * page_bytes
+    n = len(L)
+    prompts = [np.full(P, 1, np.int32) for _ in range(n)]
+    orc = make_oracle(shape, max_slots=Q, max_prompt_len=P, cap=cap, kv_pool_bytes=kvb, mode=mode,
+                      max_staleness=max_staleness, page_seed=page_seed)
+    ctx = make_engine(shape, None, max_slots=Q, max_prompt_len=P, cap=cap, max_seqs=n, kv_pool_bytes=kvb, mode=mode,
+                      max_staleness=max_staleness, page_seed=page_seed, debug_flags=R.ROLLOUT_DEBUG_NO_MODEL)
+    try:
+        toks, offs = flat_prompts(prompts)
+        assert R.rollout_submit(ctx, toks, offs, L) == orc.submit(prompts, L)
+        harvested = 0
+        while orc.queue or any(x is not None for x in orc.slots):
+            io = orc.step()
+            ig = R.rollout_step(ctx)
+            assert info_tuple(ig) == info_tuple(io), (info_tuple(ig), info_tuple(io))
+            for slot in range(0, Q, max(1, Q // 4)):                  # sampled page tables
+                s = orc.slots[slot]
+                pages = R.rollout_slot_pages(ctx, slot, 4096)
+                assert list(pages) == (s.pages if s is not None else [])
+            if harvest_every and len(orc.finished) >= G:
+                recs, *_ = _harvest_both(R, ctx, orc, G)
+                harvested += len(recs)
+        recs, tk, lp, flat = _harvest_both(R, ctx, orc, G, flush=True)
+        harvested += len(recs)
+        assert harvested == n
+        for r, s in zip(recs, flat):
+            assert list(tk[r.tok_off:r.tok_off + r.gen_len]) == s.tokens
+        _compare_stats(R, ctx, orc)
+        assert abs(R.rollout_stats(ctx).idle / (Q * R.rollout_stats(ctx).steps) - orc.bubble_ratio()) < 1e-15
+    finally:
+        R.rollout_destroy(ctx)
+
+
+def test_scheduler_bit_exact_continuous_refill():
+    L = W.make_target_lengths(96, 3.2, 0.8, 120, seed=21)
+    _scheduler_only(L, Q=12, P=20, cap=120, G=8)
+
+
+def test_scheduler_bit_exact_with_staleness_and_late_harvests():
+    L = W.make_target_lengths(80, 3.5, 0.9, 200, seed=22)
+    _scheduler_only(L, Q=16, P=7, cap=200, G=5, max_staleness=1)
+    _scheduler_only(L, Q=16, P=7, cap=200, G=5, max_staleness=0, page_seed=99)
+
+
+def test_scheduler_bit_exact_under_pool_exhaustion_and_preemption():
+    L = W.make_target_lengths(40, 4.0, 0.7, 160, seed=23)
+    # pages per max sequence = ceil((33 + 160) / 16) = 13; 30 pages for 8 slots forces preemption
+    _scheduler_only(L, Q=8, P=33, cap=160, G=4, kv_pool_pages=30)
+
+
+def test_scheduler_bit_exact_sync_baseline_and_on_policy_modes():
+    L = W.make_target_lengths(48, 3.0, 0.8, 100, seed=24)
+    _scheduler_only(L, Q=8, P=5, cap=100, G=8, mode=2)
+    _scheduler_only(L, Q=8, P=5, cap=100, G=4, mode=1)
+
+
+def test_scheduler_hand_built_preemption_case():
+    # same case as tests/test_oracle_scheduler.py: needs 4-token pages there; with 16-token pages use P = 15
+    _scheduler_only(np.array([40, 40, 40], np.int32), Q=3, P=15, cap=64, G=3, kv_pool_pages=5)
+
+
+def test_tiny_policy_teacher_forced_logits_and_scheduler():
+    """The parity gate: the 2-layer fp32-sized policy of the smallest config, every (sequence, step) logits row
+    within 2e-2 of the oracle under teacher forcing, scheduler output identical."""
+    import paper_2603_23414_amd as R
+    c = W.CONFIGS["tiny"]
+    m = c.model
+    blob = W.make_weights(m, c.seed_weights)
+    prompts = list(W.make_prompts(c.n_prompts, c.prompt_len, m.vocab, c.seed_prompts))
+    L = W.make_target_lengths(c.n_prompts, c.len_mu, c.len_sigma, c.cap, c.seed_lengths)
+    orc = make_oracle(m, max_slots=c.max_slots, max_prompt_len=c.prompt_len, cap=c.cap, weights_blob=blob)
+    ctx = make_engine(m, blob, max_slots=c.max_slots, max_prompt_len=c.prompt_len, cap=c.cap, max_seqs=c.n_prompts)
+    try:
+        toks, offs = flat_prompts(prompts)
+        R.rollout_submit(ctx, toks, offs, L)
+        orc.submit(prompts, L)
+        logits = np.zeros((c.max_slots, m.vocab), np.float32)
+        worst, rows, argmax_agree = 0.0, 0, 0
+        while orc.queue or any(x is not None for x in orc.slots):
+            before = [s.gen_len for s in orc.seqs]
+            io = orc.step()
+            forced = np.full(c.max_slots, -1, np.int32)
+            ran = {}
+            for s in orc.seqs:                                   # every sequence that emitted a token this step
+                if s.gen_len > before[s.seq_id]:
+                    forced[s.last_slot] = s.tokens[-1]
+                    ran[s.last_slot] = s
+            logits[:] = np.nan
+            ig = R.rollout_step_forced(ctx, forced, logits)
+            assert info_tuple(ig) == info_tuple(io)
+            assert len(ran) == io["r"]
+            for slot, s in ran.items():
+                ref = orc.last_logits[slot]
+                err = float(np.max(np.abs(logits[slot].astype(np.float64) - ref)))
+                worst = max(worst, err)
+                rows += 1
+                argmax_agree += int(np.argmax(logits[slot]) == int(np.argmax(ref)))
+        assert rows == int(L.sum())
+        assert worst < 2e-2, worst
+        assert argmax_agree >= 0.98 * rows
+        recs, tk, lp, flat = _harvest_both(R, ctx, orc, c.harvest, flush=True)
+        for r, s in zip(recs, flat):
+            assert list(tk[r.tok_off:r.tok_off + r.gen_len]) == s.tokens
+            assert np.max(np.abs(lp[r.tok_off:r.tok_off + r.gen_len] - np.array(s.logp))) < 3e-2
+            assert np.all(lp[r.tok_off:r.tok_off + r.gen_len] <= 1e-6)
+        _compare_stats(R, ctx, orc)
+    finally:
+        R.rollout_destroy(ctx)
+
+
+def test_tiny_policy_free_running_is_deterministic_and_matches_schedule():
+    import paper_2603_23414_amd as R
+    c = W.CONFIGS["tiny"]
+    m = c.model
+    blob = W.make_weights(m, c.seed_weights)
+    prompts = list(W.make_prompts(c.n_prompts, c.prompt_len, m.vocab, c.seed_prompts))
+    L = W.make_target_lengths(c.n_prompts, c.len_mu, c.len_sigma, c.cap, c.seed_lengths)
+    runs = []
+    for _ in range(2):
+        ctx = make_engine(m, blob, max_slots=c.max_slots, max_prompt_len=c.prompt_len, cap=c.cap, max_seqs=c.n_prompts)
+        try:
+            toks, offs = flat_prompts(prompts)
+            R.rollout_submit(ctx, toks, offs, L)
+            out = []
+            while True:
+                i = R.rollout_step(ctx)
+                if i.n_finished_unharvested >= c.harvest:
+                    ng, recs, tk, lp = R.rollout_harvest(ctx, c.harvest)
+                    out += [(r.seq_id, r.slot, r.completion_step, r.gen_len, tuple(tk[r.tok_off:r.tok_off + r.gen_len]))
+                            for r in recs]
+                if i.n_active == 0 and i.n_queued == 0:
+                    break
+            ng, recs, tk, lp = R.rollout_harvest(ctx, c.harvest, R.ROLLOUT_FLUSH)
+            out += [(r.seq_id, r.slot, r.completion_step, r.gen_len, tuple(tk[r.tok_off:r.tok_off + r.gen_len]))
+                    for r in recs]
+            runs.append(out)
+        finally:
+            R.rollout_destroy(ctx)
+    assert runs[0] == runs[1]
+    assert sorted(r[0] for r in runs[0]) == list(range(c.n_prompts))
+    assert [r[3] for r in sorted(runs[0])] == list(L)
+    orc = make_oracle(m, max_slots=c.max_slots, max_prompt_len=c.prompt_len, cap=c.cap)
+    orc.submit(prompts, L)
+    ref = [(s.seq_id, s.last_slot, s.completion_step, s.gen_len) for g in orc.run_to_completion(c.harvest) for s in g]
+    assert [r[:4] for r in runs[0]] == ref
+
+
+def test_error_paths():
+    import paper_2603_23414_amd as R
+    c = W.CONFIGS["tiny"]
+    m = c.model
+    blob = W.make_weights(m, 1)
+    ctx = make_engine(m, blob, max_slots=4, max_prompt_len=16, cap=32, max_seqs=4)
+    try:
+        with pytest.raises(R.RolloutError) as e:
+            R.rollout_submit(ctx, np.arange(17, dtype=np.int32), [0, 17], [5])
+        assert e.value.code == -4
+        with pytest.raises(R.RolloutError) as e:
+            R.rollout_submit(ctx, np.array([m.vocab], np.int32), [0, 1], [5])
+        assert e.value.code == -4
+        with pytest.raises(R.RolloutError) as e:
+            R.rollout_submit(ctx, np.zeros(5, np.int32), [0, 1, 2, 3, 4, 5], [1] * 5)
+        assert e.value.code == -3
+        assert R.rollout_harvest(ctx, 2)[0] == 0
+        R.rollout_submit(ctx, np.zeros(3, np.int32), [0, 3], [2])
+        R.rollout_step(ctx)
+        tk, lp, state, slot = R.rollout_peek(ctx, 0, 32)
+        assert len(tk) == 1 and state == 1 and slot == 0
+        R.rollout_step(ctx)
+        ng, recs, tk, lp = R.rollout_harvest(ctx, 1)
+        assert ng == 1 and recs[0].gen_len == 2 and tk[-1] == m.vocab - 1
+    finally:
+        R.rollout_destroy(ctx)
+    with pytest.raises(R.RolloutError):
+        make_engine(m, blob[:-5], max_slots=4, max_prompt_len=16, cap=32, max_seqs=4)
