@@ -30,7 +30,7 @@ def _compare_stats(R, ctx, orc):
 def _scheduler_only(L, *, Q, P, cap, G, kv_pool_pages=0, max_staleness=-1, mode=0, page_seed=0, harvest_every=True):
     """NO_MODEL run of the device scheduler against the integer oracle, step by step."""
     import paper_2603_23414_amd as R
-    shape = W.ModelShape(1, 64, 1, 1, 32, 64, 64, 1e-5, 1e4, 0)
+    shape = W.ModelShape(1, 64, 2, 2, 32, 64, 64, 1e-5, 1e4, 0)
     page_bytes = shape.n_layers * shape.n_kv_heads * 2 * 16 * shape.head_dim * 2
     kvb = kv_pool_pages * page_bytes
     n = len(L)
