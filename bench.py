@@ -1,0 +1,264 @@
+#!/usr/bin/env python3
+"""Rollout benchmark on one MI355X: `python bench.py --gpus 1 --steps K --warmup W` prints ONE JSON line.
+
+A step is one rollout_step() of the whole hot path (refill + prefill, decode of every running slot through all
+layers, LM head, argmax/EOS, eviction, page growth; harvest whenever a full update group is ready) on the
+8B-shaped, 16k-cap workload.  The timed window starts from a representative mid-run state: the integer
+scheduler (oracle, CPU, no model) is run to the step whose in-flight context is closest to the run's average,
+and that state is recreated through the public API by submitting each running rollout as prompt + already
+generated tokens (what partial mode re-feeds after an interruption); their prefill is warm-up.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+
+def device_weights(torch, m, seed):
+    """bf16 N(0, 0.02) blob in weights-blob order, generated on the GPU (norm gains 1)."""
+    import workloads as W
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(seed)
+    n = W.weight_count(m)
+    blob = torch.empty(n, dtype=torch.bfloat16, device="cuda:0")
+    off = 0
+    for name, r, c in W.weight_layout(m):
+        v = blob[off:off + r * c]
+        if name.endswith("norm"):
+            v.fill_(1.0)
+        else:
+            step = 1 << 28
+            for a in range(0, r * c, step):
+                v[a:a + step].normal_(0.0, 0.02, generator=g)
+        off += r * c
+    torch.cuda.synchronize()
+    return blob
+
+
+def scheduler_snapshot(wl, L):
+    """Run the integer scheduler oracle over the whole workload; return (snapshot for the warm start, full-run stats)."""
+    from oracle import OracleRollout
+    from tests._util import n_pages_for
+    m = wl.model
+    n_pages = n_pages_for(m, wl.max_slots, wl.prompt_len, wl.cap, wl.kv_pool_bytes)
+
+    def mk(mode=0, stale=wl.max_staleness):
+        o = OracleRollout(max_slots=wl.max_slots, page_tokens=16, n_pages=n_pages, max_new_tokens=wl.cap,
+                          eos_id=m.eos_id, max_staleness=stale, mode=mode)
+        o.submit([np.zeros(wl.prompt_len, np.int32)] * wl.n_prompts, L)
+        return o
+
+    o = mk()
+    ctx_sum = []
+    while o.queue or any(x is not None for x in o.slots):
+        o.step()
+        if len(o.finished) >= wl.harvest:
+            o.harvest(wl.harvest)
+        if o.queue:
+            ctx_sum.append(sum(len(s.prompt) + s.gen_len for s in o.slots if s is not None))
+    full = dict(steps=o.step_no, bubble=o.bubble_ratio(), n_stale=o.n_stale, n_preempt=o.n_preempt,
+                prefill_tokens=o.prefill_tokens, gen_tokens=o.gen_tokens)
+    sync = mk(mode=2, stale=-1)
+    sync.run_to_completion(wl.harvest)
+    full["bubble_sync_baseline"] = sync.bubble_ratio()
+    target = float(np.mean(ctx_sum))
+    s0 = int(np.argmin(np.abs(np.array(ctx_sum) - target)))
+    o = mk()
+    while o.step_no <= s0:
+        o.step()
+        if len(o.finished) >= wl.harvest:
+            o.harvest(wl.harvest)
+    running = [(s.seq_id, s.gen_len) for s in o.slots if s is not None]
+    queued = [(s.seq_id, s.gen_len) for s in o.queue]
+    return dict(step=s0, running=running, queued=queued, mean_ctx_sum=target), full
+
+
+def cpu_baseline(wl, ctx_lens, budget_s=20.0):
+    """The oracle as it stands (numpy, fp32), timed on this host: per-token decode time of 1- and 2-layer slices at
+    full widths, extrapolated linearly to all layers."""
+    import workloads as W
+    from oracle import ContiguousKV, OracleModel
+    t_of = {}
+    g = np.random.default_rng(0)
+    for nl in (1, 2):
+        m = wl.model.with_layers(nl)
+        w = {}
+        for name, r, c in W.weight_layout(m):
+            w[name] = np.ones((r, c), np.float32) if name.endswith("norm") else \
+                g.standard_normal((r, c), dtype=np.float32) * np.float32(0.02)
+        model = OracleModel(m, w, np.float32)
+        times = []
+        t_start = time.time()
+        for L in ctx_lens:
+            cache = ContiguousKV(nl)
+            for l in range(nl):
+                cache.k[l] = list(g.standard_normal((L, m.n_kv_heads, m.head_dim), dtype=np.float32))
+                cache.v[l] = list(g.standard_normal((L, m.n_kv_heads, m.head_dim), dtype=np.float32))
+            t0 = time.time()
+            model.token_forward(int(g.integers(0, m.vocab - 1)), int(L), cache)
+            times.append(time.time() - t0)
+            if time.time() - t_start > budget_s / 2:
+                break
+        t_of[nl] = float(np.mean(times))
+        del model, w
+    per_tok = t_of[1] + (wl.model.n_layers - 1) * max(t_of[2] - t_of[1], 0.0)
+    try:
+        import threadpoolctl
+        cores = max(int(i.get("num_threads", 1)) for i in threadpoolctl.threadpool_info()) if threadpoolctl.threadpool_info() else 1
+    except Exception:
+        cores = os.cpu_count() or 1
+    return dict(value=1.0 / per_tok, unit="tokens/s", cores=cores, kind="oracle",
+                sample=f"numpy fp32 oracle, one decode token at {len(times)} in-flight contexts "
+                       f"(mean {int(np.mean(ctx_lens[:len(times)]))} tokens), 1- and 2-layer slices at full widths, "
+                       f"extrapolated to {wl.model.n_layers} layers")
+
+
+def attention_alone(torch, R, iters=20):
+    """The decode-attention kernel alone on the 256-sequence long-tail case: HIP-event time per launch."""
+    import workloads as W
+    a = W.ATTN_CASE
+    Hq, Hkv, d, n = a["n_q_heads"], a["n_kv_heads"], a["head_dim"], a["n_seqs"]
+    lens = W.make_kv_lengths(n, a["median"], a["sigma"], a["cap"], a["seed_lengths"])
+    table, n_pool = W.make_page_table(lens, 16, a["seed_pages"])
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(a["seed_values"])
+    pools = []
+    for _ in range(3):   # rotate pools so no launch finds its KV in the 256 MB last-level cache
+        p = torch.empty(R.rollout_attn_pool_bytes(n_pool, Hkv, d) // 2, dtype=torch.bfloat16, device=dev)
+        p.normal_(0.0, 1.0, generator=g)
+        pools.append(p)
+    q = torch.empty((n, Hq, d), dtype=torch.bfloat16, device=dev).normal_(0.0, 1.0, generator=g)
+    tab = torch.from_numpy(np.maximum(table, 0).astype(np.int32)).to(dev)
+    ws_bytes = R.rollout_attn_workspace_bytes(n, int(lens.sum()), Hq, d)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    n_work = R.rollout_attn_plan(lens, Hq, d, ws.data_ptr(), ws_bytes)
+    out = torch.empty((n, Hq, d), dtype=torch.bfloat16, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def launch(i):
+        R.rollout_attn_decode(pools[i % 3].data_ptr(), Hq, Hkv, d, q.data_ptr(), tab.data_ptr(), table.shape[1], n,
+                              n_work, out.data_ptr(), 0, ws.data_ptr(), stream.cuda_stream)
+    for i in range(3):
+        launch(i)
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    for i, (e0, e1) in enumerate(evs):
+        e0.record(stream)
+        launch(i)
+        e1.record(stream)
+    torch.cuda.synchronize()
+    ms = np.array([e0.elapsed_time(e1) for e0, e1 in evs])
+    bytes_per = int(lens.sum()) * Hkv * 2 * d * 2 + 2 * n * Hq * d * 2 + int(((lens + 15) // 16).sum()) * 4
+    return dict(median_ms=float(np.median(ms)), gbps=bytes_per / np.median(ms) / 1e6, bytes=bytes_per,
+                kv_tokens=int(lens.sum()), frac_of_8TBps=bytes_per / np.median(ms) / 1e6 / 8000.0)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=60)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="8b_long")
+    ap.add_argument("--layers", type=int, default=0, help="debug: override the layer count (invalidates the result)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-attn-alone", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2603_23414_amd as R
+    import workloads as W
+    wl = W.CONFIGS[args.workload]
+    m = wl.model if not args.layers else wl.model.with_layers(args.layers)
+    L = W.make_target_lengths(wl.n_prompts, wl.len_mu, wl.len_sigma, wl.cap, wl.seed_lengths)
+    t0 = time.time()
+    snap, full = scheduler_snapshot(wl, L)
+    print(f"[bench] scheduler oracle: {full} snapshot step {snap['step']} ({time.time() - t0:.1f}s)", file=sys.stderr)
+
+    attn = None if args.no_attn_alone else attention_alone(torch, R)
+    if attn:
+        print(f"[bench] attention alone: {attn}", file=sys.stderr)
+
+    blob = device_weights(torch, m, wl.seed_weights)
+    # warm start through the public API: running rollouts first (they take slots 0..), then the queue in order
+    order = snap["running"] + snap["queued"]
+    max_prompt = wl.prompt_len + max(g for _, g in order)
+    g = W.rng(wl.seed_prompts)
+    prompts = [g.integers(0, m.vocab - 1, size=wl.prompt_len + gl, dtype=np.int64).astype(np.int32) for _, gl in order]
+    targets = np.array([int(L[sid]) - gl for sid, gl in order], np.uint32)
+    cap = int(targets.max())
+    cfg = R.make_cfg(m, max_slots=wl.max_slots, max_prompt_len=max_prompt, max_new_tokens=cap, max_seqs=len(order),
+                     kv_pool_bytes=wl.kv_pool_bytes * m.n_layers // wl.model.n_layers, weights_on_device=1,
+                     max_staleness=wl.max_staleness, debug_flags=R.ROLLOUT_DEBUG_TIME_ATTN)
+    ctx = R.rollout_init((blob.data_ptr(), blob.numel() * 2), cfg)
+    del blob
+    torch.cuda.empty_cache()
+    offs = np.zeros(len(prompts) + 1, np.uint32)
+    offs[1:] = np.cumsum([len(p) for p in prompts])
+    R.rollout_submit(ctx, np.concatenate(prompts), offs, targets)
+
+    def one_step():
+        i = R.rollout_step(ctx)
+        if i.n_finished_unharvested >= wl.harvest:
+            R.rollout_harvest(ctx, wl.harvest, 0, want_logp=True)
+        return i
+
+    t0 = time.time()
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    print(f"[bench] warm-up ({args.warmup} steps incl. warm-start prefill): {time.time() - t0:.1f}s", file=sys.stderr)
+    s0 = R.rollout_stats(ctx)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    tokens = 0
+    for _ in range(args.steps):
+        tokens += one_step().n_ran
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    s1 = R.rollout_stats(ctx)
+    R.rollout_destroy(ctx)
+
+    launches = s1.attn_launches - s0.attn_launches
+    kv_tok = s1.attn_kv_tokens - s0.attn_kv_tokens
+    attn_ms = s1.attn_ms - s0.attn_ms
+    kv_bytes_tok = m.n_kv_heads * 2 * m.head_dim * 2
+    rows_per_launch = (s1.busy - s0.busy) / max(1, args.steps)
+    alg_bytes = kv_tok * kv_bytes_tok + launches * rows_per_launch * (2 * m.n_q_heads * m.head_dim * 2)
+    achieved = alg_bytes / max(attn_ms, 1e-9) / 1e6 if launches else 0.0
+    roofline = dict(bound="hbm", kernel="k_decode_attn (ragged paged GQA decode attention, in situ)",
+                    achieved=achieved, peak=8000.0, unit="GB/s", frac=achieved / 8000.0, traffic=None,
+                    launches=int(launches), avg_launch_ms=attn_ms / max(1, launches),
+                    alg_bytes_per_launch=alg_bytes / max(1, launches))
+    out = dict(metric="rollout tokens/s (8B shape, 16k-cap lengths)", value=tokens / dt, unit="tokens/s", n_gpus=1,
+               steps=args.steps, warmup=args.warmup, ms_per_step=1e3 * dt / args.steps, higher_is_better=True,
+               scaling="weak", vs_baseline=None, dtype="bf16", data="synthetic",
+               config=dict(workload=f"{wl.name}: LLaMA-3.1-8B shape ({m.n_layers} layers), Q={wl.max_slots}, "
+                                    f"{wl.n_prompts} prompts x {wl.prompt_len}, LogNormal(median 2048, sigma 1.0) cap "
+                                    f"{wl.cap}, KV pool {wl.kv_pool_bytes / 1e9:.0f} GB, harvest {wl.harvest}, "
+                                    f"max_staleness {wl.max_staleness}; timed window from scheduler step "
+                                    f"{snap['step']} (mean in-flight context)",
+                           mean_inflight_ctx=snap["mean_ctx_sum"] / wl.max_slots,
+                           prefill_tokens_in_window=int(s1.prefill_tokens - s0.prefill_tokens),
+                           stale_evictions_in_window=int(s1.n_stale - s0.n_stale)),
+               roofline=roofline,
+               bubble_ratio=dict(whole_run_steps=full["bubble"], sync_baseline_steps=full["bubble_sync_baseline"],
+                                 window=(s1.idle - s0.idle) / max(1, wl.max_slots * (s1.steps - s0.steps)),
+                                 whole_run_n_steps=full["steps"], n_stale=full["n_stale"], n_preempt=full["n_preempt"]),
+               attn_alone=attn)
+    if not args.no_cpu_baseline:
+        live = [wl.prompt_len + gl for _, gl in snap["running"]]
+        out["cpu_baseline"] = cpu_baseline(wl, live[:: max(1, len(live) // 12)])
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

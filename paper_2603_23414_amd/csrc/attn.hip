@@ -27,7 +27,8 @@ __global__ __launch_bounds__(256) void k_decode_attn(
   constexpr int BLK = 2 * KBYTES;
   __shared__ __align__(16) uint16_t p_lds[4][G][64];
 
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: keeps q addressing scalar
   const int kvh = blockIdx.y * 4 + w;
   if (kvh >= Hkv) return;                       // whole wave leaves; no block-wide barrier below
   const int2 it = work[blockIdx.x];
@@ -86,7 +87,7 @@ __global__ __launch_bounds__(256) void k_decode_attn(
     for (int j = 0; j < 4; ++j) {
       const int tj = t0 + j * 16;
       if (tj >= tok_end) break;                 // wave-uniform
-      const int pgj = __shfl(pg, j * 16, 64);
+      const int pgj = __builtin_amdgcn_readlane(pg, j * 16);
       const uint8_t* vb = pool + ((size_t)pgj * Hkv + kvh) * BLK + KBYTES;
 #pragma unroll
       for (int half = 0; half < 2; ++half) {
