@@ -12,14 +12,19 @@
 #include "kernels.h"
 
 #define GEMM_BK 64
-#define LDS_ROW 72   // bf16 elements per LDS row: 64 + 8 padding
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+#define LDS_ROW 72   // bf16 elements per LDS row: 64 + 8 padding (144-byte stride: conflict-free 16-byte reads)
 
+// One k-step pairs MFMA k index (lane/32)*8 + e with memory k = (lane/32)*32 + j*8 + e inside the 64-wide block,
+// for A and W alike, so that every lane's four W loads of a block are 64 contiguous bytes (a row's two lanes
+// cover a whole 128-byte line per block).
 template <int MI>
-__global__ __launch_bounds__(256) void k_gemm_bf16(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
-                                                   float* __restrict__ C, int M, int N, int K, int kb_per_split) {
+__global__ __launch_bounds__(256, 2) void k_gemm_bf16(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
+                                                      float* __restrict__ C, int M, int N, int K, int kb_per_split) {
   constexpr int BM = 32 * MI;
   __shared__ __align__(16) uint16_t a_lds[2][BM * LDS_ROW];
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n_base = blockIdx.x * 128 + w * 32;
   const int m_base = blockIdx.y * BM;
   const int nkb_total = K / GEMM_BK;
@@ -27,20 +32,19 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const uint16_t* __restrict__ 
   const int nkb = min(kb_per_split, nkb_total - kb0);
   float* __restrict__ Cz = C + (size_t)blockIdx.z * M * N;
 
-  // W fragment source: row n (clamped), k offset (lane/32)*8 within each 16-wide MFMA k-step
   const int n_lane = min(n_base + (lane & 31), N - 1);
-  const uint16_t* __restrict__ wrow = W + (size_t)n_lane * K + (size_t)kb0 * GEMM_BK + (lane >> 5) * 8;
+  const uint16_t* __restrict__ wrow = W + (size_t)n_lane * K + (size_t)kb0 * GEMM_BK + (lane >> 5) * 32;
 
-  // A tile loads: thread -> (row, 16-byte column) ; MI loads per thread per tile
   const int a_col = tid & 7;
-  int a_row[MI];
   const uint16_t* a_src[MI];
+  int a_dst[MI];
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
-    a_row[i] = (tid >> 3) + i * 32;
-    const int gm = min(m_base + a_row[i], M - 1);
-    a_src[i] = A + (size_t)gm * K + (size_t)kb0 * GEMM_BK + a_col * 8;
+    const int r = (tid >> 3) + i * 32;
+    a_src[i] = A + (size_t)min(m_base + r, M - 1) * K + (size_t)kb0 * GEMM_BK + a_col * 8;
+    a_dst[i] = r * LDS_ROW + a_col * 8;
   }
+  const int a_frag = (lane & 31) * LDS_ROW + (lane >> 5) * 32;
 
   f32x16_t acc[MI];
 #pragma unroll
@@ -48,41 +52,49 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const uint16_t* __restrict__ 
 #pragma unroll
     for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
 
-  uint4 breg[2][4];
-  uint4 areg[MI];
+  u32x4 breg[3][4];   // ring over k blocks; every index below is a compile-time constant after unrolling
+  u32x4 areg[MI];
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) breg[0][ks] = *(const uint4*)(wrow + ks * 16);
+  for (int i = 0; i < MI; ++i) areg[i] = *(const u32x4*)(a_src[i]);
 #pragma unroll
-  for (int i = 0; i < MI; ++i) areg[i] = *(const uint4*)(a_src[i]);
+  for (int j = 0; j < 4; ++j) breg[0][j] = *(const u32x4*)(wrow + j * 8);
+  {
+    const size_t k1 = (size_t)min(1, nkb - 1) * GEMM_BK;
 #pragma unroll
-  for (int i = 0; i < MI; ++i) *(uint4*)&a_lds[0][a_row[i] * LDS_ROW + a_col * 8] = areg[i];
+    for (int j = 0; j < 4; ++j) breg[1][j] = *(const u32x4*)(wrow + k1 + j * 8);
+  }
+#pragma unroll
+  for (int i = 0; i < MI; ++i) *(u32x4*)&a_lds[0][a_dst[i]] = areg[i];
   __syncthreads();
 
-  for (int kb = 0; kb < nkb; ++kb) {
-    const int cur = kb & 1;
-    const bool more = kb + 1 < nkb;
-    if (more) {
-      const size_t ko = (size_t)(kb + 1) * GEMM_BK;
+  for (int kbase = 0; kbase < nkb; kbase += 3) {
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) breg[cur ^ 1][ks] = *(const uint4*)(wrow + ko + ks * 16);
+    for (int u = 0; u < 3; ++u) {
+      const int kb = kbase + u;
+      if (kb < nkb) {                                    // uniform
+        const int cur = kb & 1;
+        // prefetch: A one block ahead (to registers, then LDS), W two blocks ahead (register ring).  Past the
+        // end the last block is simply loaded again, which keeps the loop free of conditional register writes.
+        const size_t k1 = (size_t)min(kb + 1, nkb - 1) * GEMM_BK, k2 = (size_t)min(kb + 2, nkb - 1) * GEMM_BK;
 #pragma unroll
-      for (int i = 0; i < MI; ++i) areg[i] = *(const uint4*)(a_src[i] + ko);
-    }
-    const uint16_t* al = a_lds[cur] + (lane & 31) * LDS_ROW + (lane >> 5) * 8;
+        for (int i = 0; i < MI; ++i) areg[i] = *(const u32x4*)(a_src[i] + k1);
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      const bf16x8_t bf = __builtin_bit_cast(bf16x8_t, breg[cur][ks]);
+        for (int j = 0; j < 4; ++j) breg[(u + 2) % 3][j] = *(const u32x4*)(wrow + k2 + j * 8);
+        const uint16_t* al = a_lds[cur] + a_frag;
 #pragma unroll
-      for (int i = 0; i < MI; ++i) {
-        const uint4 av = *(const uint4*)(al + i * 32 * LDS_ROW + ks * 16);
-        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av), bf, acc[i], 0, 0, 0);
+        for (int j = 0; j < 4; ++j) {
+          const bf16x8_t bf = __builtin_bit_cast(bf16x8_t, breg[u][j]);
+#pragma unroll
+          for (int i = 0; i < MI; ++i) {
+            const u32x4 av = *(const u32x4*)(al + i * 32 * LDS_ROW + j * 8);
+            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av), bf, acc[i], 0, 0, 0);
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < MI; ++i) *(u32x4*)&a_lds[cur ^ 1][a_dst[i]] = areg[i];
+        __syncthreads();
       }
     }
-    if (more) {
-#pragma unroll
-      for (int i = 0; i < MI; ++i) *(uint4*)&a_lds[cur ^ 1][a_row[i] * LDS_ROW + a_col * 8] = areg[i];
-    }
-    __syncthreads();
   }
 
   // C fragment: element j of lane -> row (j/4)*8 + (lane/32)*4 + j%4, col lane%32
