@@ -274,3 +274,136 @@ void launch_write_kv(void* pool, int Hkv, int head_dim, const void* k, const voi
     hipLaunchKernelGGL((k_write_kv<32>), dim3(blocks), dim3(256), 0, st, (uint8_t*)pool, Hkv, (const uint16_t*)k,
                        (const uint16_t*)v, tok_seq, tok_pos, page_table, max_pages, n_tok);
 }
+
+// ---------------------------------------------------------------------------------------------------
+// Causal paged attention for prefill rows (refilled or resumed rollouts): a dense contraction, so it runs
+// on the matrix cores.  One wavefront = 32 consecutive query tokens of one sequence x one query head.
+// Both products are taken transposed so that a lane always owns one query row:
+//   S^T = K Q^T   (A = K tile straight from the page: lane -> key, 16-byte dim chunks; B = Q^T in registers)
+//   O^T = V^T P^T (A = V^T straight from the page: lane -> dim, token runs; B = P^T = the softmaxed S^T
+//                  accumulators, whose register order already is the k order the V loads use)
+// which keeps the online-softmax statistics, the rescaling and the final 1/l entirely lane-local.
+struct PfTile { int row0, n, slot, pos0; };
+
+template <int D>
+__global__ __launch_bounds__(64) void k_prefill_attn(const uint8_t* __restrict__ pool, const uint16_t* __restrict__ q,
+                                                     const PfTile* __restrict__ tiles, const int* __restrict__ page_table,
+                                                     int max_pages, int Hq, int Hkv, int G, uint16_t* __restrict__ out,
+                                                     float scale_log2e) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+  constexpr int KBYTES = PAGE_TOKENS * D * 2;
+  constexpr int BLK = 2 * KBYTES;
+  constexpr int NDC = D / 16;   // k-steps of the score product
+  constexpr int NMT = D / 32;   // 32-dim tiles of the output
+  const PfTile tile = tiles[blockIdx.x];
+  const int head = blockIdx.y, kvh = head / G;
+  const int lane = threadIdx.x, g = lane >> 5, c = lane & 31;
+  const int row = tile.row0 + min(c, tile.n - 1);
+  const int pos_c = tile.pos0 + c;
+  const int last_key = tile.pos0 + tile.n - 1;
+  const int last_page = last_key >> 4;
+  const int* __restrict__ pt = page_table + (size_t)tile.slot * max_pages;
+
+  bf16x8_t qf[NDC];
+  {
+    const uint16_t* qr = q + ((size_t)row * Hq + head) * D + g * 8;
+#pragma unroll
+    for (int dc = 0; dc < NDC; ++dc) qf[dc] = __builtin_bit_cast(bf16x8_t, *(const u32x4*)(qr + dc * 16));
+  }
+  f32x16_t o[NMT];
+#pragma unroll
+  for (int mt = 0; mt < NMT; ++mt)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) o[mt][j] = 0.f;
+  float m_run = NEG_BIG, l_run = 0.f;
+
+  const int n_kt = (last_key >> 5) + 1;
+  for (int kt = 0; kt < n_kt; ++kt) {
+    const int km = kt * 32 + c;
+    const int pg = pt[min(km >> 4, last_page)];
+    const uint8_t* kb = pool + ((size_t)pg * Hkv + kvh) * BLK + (km & 15) * 16 + g * 256;
+    f32x16_t s;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) s[j] = 0.f;
+#pragma unroll
+    for (int dc = 0; dc < NDC; ++dc) {
+      const bf16x8_t kf = __builtin_bit_cast(bf16x8_t, *(const u32x4*)(kb + dc * 512));
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[dc], s, 0, 0, 0);
+    }
+    // s[j] = score of key kt*32 + (j/4)*8 + g*4 + j%4 against this lane's query row
+    float mx = NEG_BIG;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const int key = kt * 32 + (j >> 2) * 8 + g * 4 + (j & 3);
+      s[j] = key <= pos_c ? s[j] * scale_log2e : NEG_BIG;
+      mx = fmaxf(mx, s[j]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    m_run = m_new;
+    float ls = 0.f;
+    uint32_t pk[8];
+#pragma unroll
+    for (int j = 0; j < 16; j += 2) {
+      // a fully masked row (query rows past the tile's valid count never are) would give exp2(0) here; key 0 is
+      // always visible to every valid row, so m_new is a real score
+      const float p0 = s[j] > -1.0e29f ? __builtin_amdgcn_exp2f(s[j] - m_new) : 0.f;
+      const float p1 = s[j + 1] > -1.0e29f ? __builtin_amdgcn_exp2f(s[j + 1] - m_new) : 0.f;
+      ls += p0 + p1;
+      pk[j >> 1] = pack_bf2(p0, p1);
+    }
+    l_run = l_run * alpha + ls;
+#pragma unroll
+    for (int mt = 0; mt < NMT; ++mt)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) o[mt][j] *= alpha;
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) {
+      if (kt * 32 + s2 * 16 > last_key) break;          // wave-uniform: page wholly past the tile's last query
+      const int pgs = __builtin_amdgcn_readlane(pg, s2 * 16);
+      const uint8_t* vb = pool + ((size_t)pgs * Hkv + kvh) * BLK + KBYTES + g * 8;
+      u32x4 pw;
+      pw.x = pk[4 * s2]; pw.y = pk[4 * s2 + 1]; pw.z = pk[4 * s2 + 2]; pw.w = pk[4 * s2 + 3];
+      const bf16x8_t pf = __builtin_bit_cast(bf16x8_t, pw);
+#pragma unroll
+      for (int mt = 0; mt < NMT; ++mt) {
+        const int dim = mt * 32 + c;
+        const u32x2 lo = *(const u32x2*)(vb + (size_t)dim * 16);
+        const u32x2 hi = *(const u32x2*)(vb + (size_t)(D + dim) * 16);
+        u32x4 vw;
+        vw.x = lo.x; vw.y = lo.y; vw.z = hi.x; vw.w = hi.y;
+        o[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vw), pf, o[mt], 0, 0, 0);
+      }
+    }
+  }
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  if (c < tile.n) {
+    const float inv = 1.f / l_tot;
+    uint16_t* orow = out + ((size_t)(tile.row0 + c) * Hq + head) * D;
+#pragma unroll
+    for (int mt = 0; mt < NMT; ++mt)
+#pragma unroll
+      for (int jq = 0; jq < 4; ++jq) {
+        const int dim = mt * 32 + jq * 8 + g * 4;
+        u32x2 w2;
+        w2.x = pack_bf2(o[mt][jq * 4] * inv, o[mt][jq * 4 + 1] * inv);
+        w2.y = pack_bf2(o[mt][jq * 4 + 2] * inv, o[mt][jq * 4 + 3] * inv);
+        *(u32x2*)(orow + dim) = w2;
+      }
+  }
+}
+
+void launch_prefill_attn(const void* pool, const void* q, const void* tiles, int n_tiles, const int* page_table,
+                         int max_pages, int Hq, int Hkv, int head_dim, void* out, hipStream_t st) {
+  if (n_tiles <= 0) return;
+  const float scale = 1.4426950408889634f / sqrtf((float)head_dim);
+  dim3 grid(n_tiles, Hq);
+  if (head_dim == 128)
+    hipLaunchKernelGGL((k_prefill_attn<128>), grid, dim3(64), 0, st, (const uint8_t*)pool, (const uint16_t*)q,
+                       (const PfTile*)tiles, page_table, max_pages, Hq, Hkv, Hq / Hkv, (uint16_t*)out, scale);
+  else
+    hipLaunchKernelGGL((k_prefill_attn<32>), grid, dim3(64), 0, st, (const uint8_t*)pool, (const uint16_t*)q,
+                       (const PfTile*)tiles, page_table, max_pages, Hq, Hkv, Hq / Hkv, (uint16_t*)out, scale);
+}

@@ -16,7 +16,6 @@
 #include "kernels.h"
 
 #define PF_ROWS 4096          // token rows per prefill pass
-#define PF_MAX_WORK 32768     // attention work items per prefill pass
 
 namespace {
 
@@ -75,9 +74,9 @@ struct rollout_ctx {
   float* row_lse = nullptr;
   int* iota = nullptr;
   // prefill rows + attention workspace
-  int *pf_row_slot = nullptr, *pf_row_pos = nullptr, *pf_row_tok = nullptr, *pf_row_wstart = nullptr;
-  int2* pf_work = nullptr;
-  int* pf_last_rows = nullptr;
+  int *pf_row_slot = nullptr, *pf_row_pos = nullptr, *pf_row_tok = nullptr;
+  PfTileHost* pf_tiles_dev = nullptr;
+  PfTileHost* pf_tiles_host = nullptr;  // pinned
   PrefillDesc* pf_desc_dev = nullptr;
   PrefillDesc* pf_desc_host = nullptr;  // pinned
   int* pf_last_host = nullptr;          // pinned
@@ -235,7 +234,7 @@ int load_weights(rollout_ctx* c, const void* weights, size_t weights_bytes) {
 
 // ---- the per-step kernel chain over a set of rows (decode rows or one prefill pass) ---------------------
 void run_layers(rollout_ctx* c, int R, const int* row_slot, const int* row_pos, const int* row_tok, const int2* work,
-                const int* row_wstart, int n_work, bool time_attn) {
+                const int* row_wstart, int n_work, bool time_attn, const PfTileHost* pf_tiles = nullptr, int n_tiles = 0) {
   hipStream_t st = c->stream;
   const int D = c->D, F = c->F, Hq = c->Hq, Hkv = c->Hkv, d = c->d, Nqkv = c->Nqkv;
   const float eps = c->cfg.rms_eps;
@@ -266,9 +265,13 @@ void run_layers(rollout_ctx* c, int R, const int* row_slot, const int* row_pos, 
     a.out = c->attn_out;
     a.out_fp32 = 0;
     a.need_merge = n_work > R;
-    if (time_attn) (void)hipEventRecord(c->ev[2 * l], st);
-    launch_decode_attn(a, d, c->G, st);
-    if (time_attn) (void)hipEventRecord(c->ev[2 * l + 1], st);
+    if (n_tiles > 0) {
+      launch_prefill_attn(pool_l, c->qbuf, pf_tiles, n_tiles, c->sd.page_table, c->max_pages, Hq, Hkv, d, c->attn_out, st);
+    } else {
+      if (time_attn) (void)hipEventRecord(c->ev[2 * l], st);
+      launch_decode_attn(a, d, c->G, st);
+      if (time_attn) (void)hipEventRecord(c->ev[2 * l + 1], st);
+    }
     launch_gemm(c->attn_out, L.wo, c->part, R, D, Hq * d, S2, st);
     launch_add_rmsnorm(c->h, c->part, S2, (size_t)R * D, L.ffn_norm, eps, c->x, R, D, st);
     launch_gemm(c->x, L.wgu, c->part, R, 2 * F, D, S3, st);
@@ -279,33 +282,20 @@ void run_layers(rollout_ctx* c, int R, const int* row_slot, const int* row_pos, 
   }
 }
 
-// attention work items of positions [p0, p1) of one sequence
-inline long long work_items(int p0, int p1) {
-  long long s = 0;
-  for (int p = p0; p < p1; ++p) s += (p + 1 + ATTN_CHUNK - 1) / ATTN_CHUNK;
-  return s;
-}
-
 int run_prefill(rollout_ctx* c, int n_dec, int n_adm) {
   // admitted sequences in ascending slot order: (slot, sidx, n_tok) triples in the status block
   const int* desc = c->status_host + STAT_HDR;
   int a = 0, pos = 0;  // cursor: sequence a, next position pos
+  hipStream_t st = c->stream;
   while (a < n_adm) {
-    int rows = 0, n_desc = 0, n_last = 0;
-    long long items = 0;
+    int rows = 0, n_desc = 0, n_last = 0, n_tiles = 0;
     while (a < n_adm && rows < PF_ROWS) {
       const int slot = desc[3 * a], sidx = desc[3 * a + 1], n = desc[3 * a + 2];
-      int take = std::min(n - pos, PF_ROWS - rows);
-      // shrink the piece until its attention work fits the pass
-      long long w = work_items(pos, pos + take);
-      while (take > 1 && items + w > PF_MAX_WORK) {
-        take = std::max(1, take / 2);
-        w = work_items(pos, pos + take);
-      }
-      if (items + w > PF_MAX_WORK && rows > 0) break;
+      const int take = std::min(n - pos, PF_ROWS - rows);
       c->pf_desc_host[n_desc++] = PrefillDesc{slot, sidx, take, pos, rows};
+      for (int t = 0; t < take; t += 32)   // query tiles of up to 32 consecutive tokens
+        c->pf_tiles_host[n_tiles++] = PfTileHost{rows + t, std::min(32, take - t), slot, pos + t};
       rows += take;
-      items += w;
       pos += take;
       if (pos == n) {
         c->pf_last_host[2 * n_last] = rows - 1;   // row holding the sequence's last token
@@ -314,19 +304,17 @@ int run_prefill(rollout_ctx* c, int n_dec, int n_adm) {
         ++a;
         pos = 0;
       }
-      if (items >= PF_MAX_WORK) break;
     }
-    hipStream_t st = c->stream;
     HIPCHK(c, hipMemcpyAsync(c->pf_desc_dev, c->pf_desc_host, sizeof(PrefillDesc) * n_desc, hipMemcpyHostToDevice, st));
+    HIPCHK(c, hipMemcpyAsync(c->pf_tiles_dev, c->pf_tiles_host, sizeof(PfTileHost) * n_tiles, hipMemcpyHostToDevice, st));
     launch_prefill_rows(c->sd, c->pf_desc_dev, n_desc, c->pf_row_slot, c->pf_row_pos, c->pf_row_tok, st);
-    launch_attn_worklist(c->pf_row_pos, rows, c->pf_work, c->pf_row_wstart, nullptr, st);
-    run_layers(c, rows, c->pf_row_slot, c->pf_row_pos, c->pf_row_tok, c->pf_work, c->pf_row_wstart, (int)items, false);
+    run_layers(c, rows, c->pf_row_slot, c->pf_row_pos, c->pf_row_tok, nullptr, nullptr, 0, false, c->pf_tiles_dev, n_tiles);
     for (int j = 0; j < n_last; ++j) {
       // one tiny gather per finished prompt: h row -> h_final row n_dec + (index among admitted)
       const int src_row = c->pf_last_host[2 * j], dst = n_dec + c->pf_last_host[2 * j + 1];
       launch_gather_rows(c->h, c->iota + src_row, c->h_final, dst, 1, c->D, st);
     }
-    // the pinned descriptor buffer is reused by the next pass
+    // the pinned descriptor buffers are reused by the next pass
     HIPCHK(c, hipStreamSynchronize(st));
   }
   return 0;
@@ -576,9 +564,9 @@ int rollout_init(rollout_ctx** out, const void* weights, size_t weights_bytes, c
     INIT_TRY(dev_alloc(c, &c->pf_row_slot, (size_t)PF_ROWS));
     INIT_TRY(dev_alloc(c, &c->pf_row_pos, (size_t)PF_ROWS));
     INIT_TRY(dev_alloc(c, &c->pf_row_tok, (size_t)PF_ROWS));
-    INIT_TRY(dev_alloc(c, &c->pf_row_wstart, (size_t)PF_ROWS));
-    c->max_work = std::max<size_t>(dec_work, (size_t)PF_MAX_WORK + 128);
-    INIT_TRY(dev_alloc(c, &c->pf_work, c->max_work));
+    c->max_work = dec_work;
+    INIT_TRY(dev_alloc(c, &c->pf_tiles_dev, (size_t)PF_ROWS));
+    INIT_TRY(host_alloc(c, &c->pf_tiles_host, (size_t)PF_ROWS));
     INIT_TRY(dev_alloc(c, &c->pf_desc_dev, (size_t)PF_ROWS));
     INIT_TRY(host_alloc(c, &c->pf_desc_host, (size_t)PF_ROWS));
     INIT_TRY(host_alloc(c, &c->pf_last_host, (size_t)2 * PF_ROWS));

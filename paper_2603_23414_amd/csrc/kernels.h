@@ -27,6 +27,11 @@ void launch_decode_attn(const AttnArgs& a, int head_dim, int group, hipStream_t 
 void launch_write_kv(void* pool, int Hkv, int head_dim, const void* k, const void* v, const int* tok_seq,
                      const int* tok_pos, const int* page_table, int max_pages, size_t n_tok, hipStream_t st);
 
+// causal paged attention for prefill rows: one tile = up to 32 consecutive query tokens of one sequence
+struct PfTileHost { int row0, n, slot, pos0; };
+void launch_prefill_attn(const void* pool, const void* q, const void* tiles, int n_tiles, const int* page_table,
+                         int max_pages, int Hq, int Hkv, int head_dim, void* out, hipStream_t st);
+
 // ---- GEMM ---------------------------------------------------------------------------------------------
 int gemm_pick_splits(int M, int N, int K);
 void launch_gemm(const void* A, const void* W, float* C, int M, int N, int K, int S, hipStream_t st);
