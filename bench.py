@@ -155,9 +155,21 @@ def attention_alone(torch, R, iters=20):
         e1.record(stream)
     torch.cuda.synchronize()
     ms = np.array([e0.elapsed_time(e1) for e0, e1 in evs])
+    # practical ceiling: a pure 16-byte-per-lane read of the same pools (rotated), same event timing
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    pool_bytes = pools[0].numel() * 2 // 16 * 16
+    rd = []
+    for i in range(6):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        R.rollout_stream_read(pools[i % 3].data_ptr(), pool_bytes, sink.data_ptr(), stream.cuda_stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        rd.append(pool_bytes / e0.elapsed_time(e1) / 1e6)
     bytes_per = int(lens.sum()) * Hkv * 2 * d * 2 + 2 * n * Hq * d * 2 + int(((lens + 15) // 16).sum()) * 4
     return dict(median_ms=float(np.median(ms)), gbps=bytes_per / np.median(ms) / 1e6, bytes=bytes_per,
-                kv_tokens=int(lens.sum()), frac_of_8TBps=bytes_per / np.median(ms) / 1e6 / 8000.0)
+                kv_tokens=int(lens.sum()), frac_of_8TBps=bytes_per / np.median(ms) / 1e6 / 8000.0,
+                pure_read_ceiling_gbps=float(np.median(rd[2:])))
 
 
 def main():

@@ -45,7 +45,7 @@ enum { ROLLOUT_MODE_PARTIAL = 0, ROLLOUT_MODE_ONPOLICY = 1, ROLLOUT_MODE_SYNC = 
 enum { ROLLOUT_FLUSH = 1 };
 enum {
   ROLLOUT_DEBUG_NO_MODEL = 1,   /* scheduler kernels only: every non-forced token is 0 */
-  ROLLOUT_DEBUG_TIME_ATTN = 2   /* bracket each decode-attention launch with HIP events (see rollout_stats) */
+  ROLLOUT_DEBUG_TIME_ATTN = 2   /* bracket each decode-attention kernel launch (not its merge) with HIP events */
 };
 
 typedef struct rollout_cfg {
@@ -198,6 +198,13 @@ int rollout_attn_decode(const void* pool_dev, uint32_t n_q_heads, uint32_t n_kv_
 uint64_t rollout_gemm_workspace_bytes(uint32_t M, uint32_t N, uint32_t K);
 int rollout_gemm_bf16(const void* a_dev, const void* w_dev, float* c_dev, uint32_t M, uint32_t N, uint32_t K,
                       void* workspace_dev, uint64_t workspace_bytes, void* stream);
+
+/* ---- plain streaming kernels: dst = src, and a pure read of src (16-byte accesses, grid-stride).  They exist to
+ * calibrate the memory-traffic counters against a known byte count and to measure the practical HBM ceiling that the
+ * KV and weight streams of the rollout step (Sec. 2.2) are compared with.  bytes must be a multiple of 16;
+ * sink_dev needs 4 writable bytes.  Enqueue only. */
+int rollout_stream_copy(const void* src_dev, void* dst_dev, uint64_t bytes, void* stream);
+int rollout_stream_read(const void* src_dev, uint64_t bytes, void* sink_dev, void* stream);
 
 #ifdef __cplusplus
 }

@@ -15,7 +15,8 @@ __all__ = [
     "rollout_init", "rollout_submit", "rollout_step", "rollout_step_forced", "rollout_harvest", "rollout_stats",
     "rollout_peek", "rollout_slot_pages", "rollout_destroy", "rollout_last_error",
     "rollout_attn_pool_bytes", "rollout_attn_write_kv", "rollout_attn_workspace_bytes", "rollout_attn_plan",
-    "rollout_attn_decode", "rollout_gemm_workspace_bytes", "rollout_gemm_bf16", "make_cfg",
+    "rollout_attn_decode", "rollout_gemm_workspace_bytes", "rollout_gemm_bf16", "rollout_stream_copy",
+    "rollout_stream_read", "make_cfg",
     "ROLLOUT_FLUSH", "ROLLOUT_DEBUG_NO_MODEL", "ROLLOUT_DEBUG_TIME_ATTN", "ROLLOUT_MODE_PARTIAL",
     "ROLLOUT_MODE_ONPOLICY", "ROLLOUT_MODE_SYNC", "ROLLOUT_EOS_FORCED_ONLY", "ROLLOUT_EOS_NATURAL_OR_FORCED",
     "EXPORTS",
@@ -37,7 +38,7 @@ EXPORTS = [
     "rollout_init", "rollout_submit", "rollout_step", "rollout_harvest", "rollout_stats", "rollout_step_forced",
     "rollout_peek", "rollout_slot_pages", "rollout_last_error", "rollout_destroy", "rollout_attn_pool_bytes",
     "rollout_attn_write_kv", "rollout_attn_workspace_bytes", "rollout_attn_plan", "rollout_attn_decode",
-    "rollout_gemm_workspace_bytes", "rollout_gemm_bf16",
+    "rollout_gemm_workspace_bytes", "rollout_gemm_bf16", "rollout_stream_copy", "rollout_stream_read",
 ]
 
 
@@ -101,6 +102,10 @@ lib.rollout_attn_decode.argtypes = [_vp, _u32, _u32, _u32, _vp, _vp, _u32, _u32,
 lib.rollout_gemm_workspace_bytes.argtypes = [_u32, _u32, _u32]
 lib.rollout_gemm_workspace_bytes.restype = _u64
 lib.rollout_gemm_bf16.argtypes = [_vp, _vp, _vp, _u32, _u32, _u32, _vp, _u64, _vp]
+
+
+lib.rollout_stream_copy.argtypes = [_vp, _vp, _u64, _vp]
+lib.rollout_stream_read.argtypes = [_vp, _u64, _vp, _vp]
 
 
 def rollout_last_error(ctx=None) -> str:
@@ -245,3 +250,11 @@ def rollout_gemm_workspace_bytes(M, N, K) -> int:
 
 def rollout_gemm_bf16(a_dev, w_dev, c_dev, M, N, K, workspace_dev, workspace_bytes, stream=0) -> None:
     _check(lib.rollout_gemm_bf16(a_dev, w_dev, c_dev, M, N, K, workspace_dev, workspace_bytes, stream))
+
+
+def rollout_stream_copy(src_dev, dst_dev, nbytes, stream=0) -> None:
+    _check(lib.rollout_stream_copy(src_dev, dst_dev, nbytes, stream))
+
+
+def rollout_stream_read(src_dev, nbytes, sink_dev, stream=0) -> None:
+    _check(lib.rollout_stream_read(src_dev, nbytes, sink_dev, stream))

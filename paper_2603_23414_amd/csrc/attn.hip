@@ -51,16 +51,36 @@ __global__ __launch_bounds__(256) void k_decode_attn(
     for (int dd = 0; dd < DPL; ++dd) acc[h][dd] = 0.f;
   }
 
+  // page ids of the whole chunk, fetched once: lane i (mod 16) holds logical page chunk*16 + i
+  const int pgs = pt[min(chunk * (ATTN_CHUNK / PAGE_TOKENS) + (lane & 15), last_page)];
+
   for (int t0 = tok0; t0 < tok_end; t0 += 64) {
-    // ---- scores: lane = token -----------------------------------------------------------------
+    const int tile = (t0 - tok0) >> 6;
+    const int pg0 = __builtin_amdgcn_readlane(pgs, tile * 4 + 0), pg1 = __builtin_amdgcn_readlane(pgs, tile * 4 + 1),
+              pg2 = __builtin_amdgcn_readlane(pgs, tile * 4 + 2), pg3 = __builtin_amdgcn_readlane(pgs, tile * 4 + 3);
+    const int pgv[4] = {pg0, pg1, pg2, pg3};
+    // ---- issue every load of the tile up front: K rows (lane = token), then V (lane = dim) ------------
     const int tok = t0 + lane;
-    const int pg = pt[min(tok >> 4, last_page)];
+    const int grp = lane >> 4;
+    const int pg = grp == 0 ? pg0 : grp == 1 ? pg1 : grp == 2 ? pg2 : pg3;
     const uint8_t* kb = pool + ((size_t)pg * Hkv + kvh) * BLK + (tok & 15) * 16;
     uint4 kr[NCH];
 #pragma unroll
     for (int c = 0; c < NCH; ++c) kr[c] = *(const uint4*)(kb + c * 256);
+    uint4 vr[4][2][DPL];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint8_t* vb = pool + ((size_t)pgv[j] * Hkv + kvh) * BLK + KBYTES;
+#pragma unroll
+      for (int half = 0; half < 2; ++half)
+#pragma unroll
+        for (int dd = 0; dd < DPL; ++dd) {
+          const int dim = (D >= 64) ? lane + dd * 64 : (lane & (D - 1));
+          vr[j][half][dd] = *(const uint4*)(vb + ((size_t)half * D + dim) * 16);
+        }
+    }
+    // ---- scores -----------------------------------------------------------------------------------------
     const bool valid = tok < tok_end;
-    float p[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) {
       float s = 0.f;
@@ -75,49 +95,46 @@ __global__ __launch_bounds__(256) void k_decode_attn(
       s = valid ? s * scale_log2e : NEG_BIG;
       const float m_new = fmaxf(m[h], wave_max(s));
       const float alpha = __builtin_amdgcn_exp2f(m[h] - m_new);
-      p[h] = valid ? __builtin_amdgcn_exp2f(s - m_new) : 0.f;
-      l[h] = l[h] * alpha + p[h];
+      const float p = valid ? __builtin_amdgcn_exp2f(s - m_new) : 0.f;
+      l[h] = l[h] * alpha + p;
       m[h] = m_new;
 #pragma unroll
       for (int dd = 0; dd < DPL; ++dd) acc[h][dd] *= alpha;
-      p_lds[w][h][lane] = f2bf(p[h]);
+      p_lds[w][h][lane] = f2bf(p);
     }
-    // ---- values: lane = output dim, operands = (token pair) x (probability pair) ---------------
+    // ---- values: operands = (token pair) x (probability pair) ---------------------------------------------
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int tj = t0 + j * 16;
-      if (tj >= tok_end) break;                 // wave-uniform
-      const int pgj = __builtin_amdgcn_readlane(pg, j * 16);
-      const uint8_t* vb = pool + ((size_t)pgj * Hkv + kvh) * BLK + KBYTES;
 #pragma unroll
       for (int half = 0; half < 2; ++half) {
         const int tb = tj + half * 8;
-        if (tb >= tok_end) break;               // wave-uniform
-        uint4 pw[G];
+        if (tb < tok_end) {                       // wave-uniform
+          uint4 pw[G];
 #pragma unroll
-        for (int h = 0; h < G; ++h) pw[h] = *(const uint4*)&p_lds[w][h][j * 16 + half * 8];
+          for (int h = 0; h < G; ++h) pw[h] = *(const uint4*)&p_lds[w][h][j * 16 + half * 8];
 #pragma unroll
-        for (int dd = 0; dd < DPL; ++dd) {
-          const int dim = lane + dd * 64;
-          if (D >= 64 || dim < D) {
-            uint4 v = *(const uint4*)(vb + ((size_t)half * D + dim) * 16);
-            if (tb + 8 > tok_end) {             // ragged tail: bytes past the context may hold anything
-              const int nv = tok_end - tb;      // 1..7 valid tokens
-              uint32_t* vw = (uint32_t*)&v;
+          for (int dd = 0; dd < DPL; ++dd) {
+            if (D >= 64 || lane < D) {
+              uint4 v = vr[j][half][dd];
+              if (tb + 8 > tok_end) {             // ragged tail: bytes past the context may hold anything
+                const int nv = tok_end - tb;      // 1..7 valid tokens
+                uint32_t* vw = (uint32_t*)&v;
 #pragma unroll
-              for (int i = 0; i < 4; ++i) {
-                const uint32_t keep = (2 * i < nv ? 0x0000FFFFu : 0u) | (2 * i + 1 < nv ? 0xFFFF0000u : 0u);
-                vw[i] &= keep;
+                for (int i = 0; i < 4; ++i) {
+                  const uint32_t keep = (2 * i < nv ? 0x0000FFFFu : 0u) | (2 * i + 1 < nv ? 0xFFFF0000u : 0u);
+                  vw[i] &= keep;
+                }
               }
-            }
 #pragma unroll
-            for (int h = 0; h < G; ++h) {
-              float a = acc[h][dd];
-              a = dot2_bf16(v.x, pw[h].x, a);
-              a = dot2_bf16(v.y, pw[h].y, a);
-              a = dot2_bf16(v.z, pw[h].z, a);
-              a = dot2_bf16(v.w, pw[h].w, a);
-              acc[h][dd] = a;
+              for (int h = 0; h < G; ++h) {
+                float a = acc[h][dd];
+                a = dot2_bf16(v.x, pw[h].x, a);
+                a = dot2_bf16(v.y, pw[h].y, a);
+                a = dot2_bf16(v.z, pw[h].z, a);
+                a = dot2_bf16(v.w, pw[h].w, a);
+                acc[h][dd] = a;
+              }
             }
           }
         }
@@ -169,7 +186,24 @@ __global__ void k_attn_merge(const int* __restrict__ row_pos, const int* __restr
   float mx = NEG_BIG;
   for (int c = 0; c < n; ++c) mx = fmaxf(mx, part_ml[((size_t)(ws + c) * Hq + head) * 2]);
   float num = 0.f, den = 0.f;
-  for (int c = 0; c < n; ++c) {
+  int c = 0;
+  for (; c + 4 <= n; c += 4) {                 // four independent partials in flight
+    float a[4], mm[4], ll[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const size_t pi = (size_t)(ws + c + u) * Hq + head;
+      mm[u] = part_ml[pi * 2];
+      ll[u] = part_ml[pi * 2 + 1];
+      a[u] = part_acc[pi * D + dim];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {              // fixed order: the result does not depend on scheduling
+      const float wgt = __builtin_amdgcn_exp2f(mm[u] - mx);
+      den += wgt * ll[u];
+      num += wgt * a[u];
+    }
+  }
+  for (; c < n; ++c) {
     const size_t pi = (size_t)(ws + c) * Hq + head;
     const float wgt = __builtin_amdgcn_exp2f(part_ml[pi * 2] - mx);
     den += wgt * part_ml[pi * 2 + 1];
@@ -242,24 +276,27 @@ void launch_attn_worklist(const int* row_pos, int n_rows, int2* work, int* row_w
 }
 
 template <int D, int G>
-static void launch_attn_t(const AttnArgs& a, hipStream_t st) {
+static void launch_attn_t(const AttnArgs& a, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   const float scale = 1.4426950408889634f / sqrtf((float)D);
   dim3 grid(a.n_work, (a.Hkv + 3) / 4);
+  if (ev0) (void)hipEventRecord(ev0, st);
   hipLaunchKernelGGL((k_decode_attn<D, G>), grid, dim3(256), 0, st, (const uint8_t*)a.pool, (const uint16_t*)a.q,
                      a.row_slot, a.row_pos, a.page_table, a.max_pages, a.work, a.Hkv, a.part_acc, a.part_ml, a.out,
                      a.out_fp32, scale);
+  if (ev1) (void)hipEventRecord(ev1, st);
   if (a.need_merge)
     hipLaunchKernelGGL((k_attn_merge<D>), dim3(a.n_rows, a.Hkv * G), dim3(D), 0, st, a.row_pos, a.row_wstart,
                        a.Hkv * G, a.part_acc, a.part_ml, a.out, a.out_fp32);
 }
 
-void launch_decode_attn(const AttnArgs& a, int head_dim, int group, hipStream_t st) {
+// ev0 / ev1 (nullable) bracket the main kernel only, not the merge.
+void launch_decode_attn(const AttnArgs& a, int head_dim, int group, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   if (a.n_work <= 0) return;
-  if (head_dim == 128 && group == 4) launch_attn_t<128, 4>(a, st);
-  else if (head_dim == 128 && group == 5) launch_attn_t<128, 5>(a, st);
-  else if (head_dim == 128 && group == 1) launch_attn_t<128, 1>(a, st);
-  else if (head_dim == 32 && group == 1) launch_attn_t<32, 1>(a, st);
-  else if (head_dim == 32 && group == 4) launch_attn_t<32, 4>(a, st);
+  if (head_dim == 128 && group == 4) launch_attn_t<128, 4>(a, st, ev0, ev1);
+  else if (head_dim == 128 && group == 5) launch_attn_t<128, 5>(a, st, ev0, ev1);
+  else if (head_dim == 128 && group == 1) launch_attn_t<128, 1>(a, st, ev0, ev1);
+  else if (head_dim == 32 && group == 1) launch_attn_t<32, 1>(a, st, ev0, ev1);
+  else if (head_dim == 32 && group == 4) launch_attn_t<32, 4>(a, st, ev0, ev1);
 }
 
 void launch_write_kv(void* pool, int Hkv, int head_dim, const void* k, const void* v, const int* tok_seq,

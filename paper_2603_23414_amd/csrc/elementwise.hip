@@ -1,5 +1,5 @@
 // The small fused kernels around the projections: embedding gather, residual-add + RMSNorm (+ bf16 cast),
-// RoPE + KV page write, SiLU*mul, arg-max / log-sum-exp over the vocabulary, row gather.
+// RoPE + KV page write, arg-max / log-sum-exp over the vocabulary, row gather.
 // All of them are HBM-trivial next to the weight and KV streams; each one also folds in the fixed-order
 // sum over the split-K partials of the projection that feeds it.
 #include "common.h"
@@ -12,48 +12,59 @@ __global__ __launch_bounds__(256) void k_embed(const uint16_t* __restrict__ tabl
   for (int i = threadIdx.x; i < D; i += 256) h[(size_t)r * D + i] = bf2f(src[i]);
 }
 
-__device__ __forceinline__ float block_sum_256(float v, float* sh) {
+__device__ __forceinline__ float block_sum_1024(float v, float* sh) {
   v = wave_sum(v);
   if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
   __syncthreads();
-  const float t = sh[0] + sh[1] + sh[2] + sh[3];
+  float t = 0.f;
+#pragma unroll
+  for (int k = 0; k < 16; ++k) t += sh[k];
   __syncthreads();
   return t;
 }
 
 // h[r] += sum_s part[s][r] (S may be 0), then x[r] = bf16( h[r] * rsqrt(mean(h[r]^2) + eps) * gain ).
-__global__ __launch_bounds__(256) void k_add_rmsnorm(float* __restrict__ h, const float* __restrict__ part, int S,
-                                                     size_t part_stride, const float* __restrict__ gain, float eps,
-                                                     uint16_t* __restrict__ x, int D) {
-  __shared__ float sh[4];
+// One 1024-thread block per row, 16-byte accesses; D is a multiple of 4 and at most 8192.
+__global__ __launch_bounds__(1024) void k_add_rmsnorm(float* __restrict__ h, const float* __restrict__ part, int S,
+                                                      size_t part_stride, const float* __restrict__ gain, float eps,
+                                                      uint16_t* __restrict__ x, int D) {
+  __shared__ float sh[16];
   const int r = blockIdx.x;
-  float v[32];
+  const int nv = D >> 2;
+  float4 v[2];
   float ss = 0.f;
 #pragma unroll
-  for (int i = 0; i < 32; ++i) {
-    const int c = threadIdx.x + i * 256;
-    if (c < D) {
-      float t = h[(size_t)r * D + c];
-      for (int s = 0; s < S; ++s) t += part[(size_t)s * part_stride + (size_t)r * D + c];
+  for (int i = 0; i < 2; ++i) {
+    const int c = threadIdx.x + i * 1024;
+    if (c < nv) {
+      float4 t = ((const float4*)(h + (size_t)r * D))[c];
+      for (int s = 0; s < S; ++s) {
+        const float4 p = ((const float4*)(part + (size_t)s * part_stride + (size_t)r * D))[c];
+        t.x += p.x; t.y += p.y; t.z += p.z; t.w += p.w;
+      }
       v[i] = t;
-      ss += t * t;
+      ss += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
     }
   }
-  const float tot = block_sum_256(ss, sh);
+  const float tot = block_sum_1024(ss, sh);
   const float inv = 1.0f / sqrtf(tot / (float)D + eps);
 #pragma unroll
-  for (int i = 0; i < 32; ++i) {
-    const int c = threadIdx.x + i * 256;
-    if (c < D) {
-      if (S > 0) h[(size_t)r * D + c] = v[i];
-      x[(size_t)r * D + c] = f2bf(v[i] * inv * gain[c]);
+  for (int i = 0; i < 2; ++i) {
+    const int c = threadIdx.x + i * 1024;
+    if (c < nv) {
+      if (S > 0) ((float4*)(h + (size_t)r * D))[c] = v[i];
+      const float4 g = ((const float4*)gain)[c];
+      uint2 o;
+      o.x = pack_bf2(v[i].x * inv * g.x, v[i].y * inv * g.y);
+      o.y = pack_bf2(v[i].z * inv * g.z, v[i].w * inv * g.w);
+      ((uint2*)(x + (size_t)r * D))[c] = o;
     }
   }
 }
 
 // qkv[r] = sum_s part[s][r] (+ bias); rotate-half RoPE on q and k heads at row_pos[r]; q -> bf16 [R][Hq][d];
 // k, v -> the slot's KV page (K as [d/8][16][8], V as [2][d][8]).
-__global__ __launch_bounds__(256) void k_rope_kvwrite(const float* __restrict__ part, int S, size_t part_stride,
+__global__ __launch_bounds__(1024) void k_rope_kvwrite(const float* __restrict__ part, int S, size_t part_stride,
                                                       const float* __restrict__ bias, const int* __restrict__ row_slot,
                                                       const int* __restrict__ row_pos, const float2* __restrict__ cs_table,
                                                       uint16_t* __restrict__ q_out, uint8_t* __restrict__ pool,
@@ -69,7 +80,7 @@ __global__ __launch_bounds__(256) void k_rope_kvwrite(const float* __restrict__ 
   const int tk = pos & 15;
   const size_t kbytes = (size_t)PAGE_TOKENS * d * 2;
   const int n_rot = (Hq + Hkv) * half;
-  for (int e = threadIdx.x; e < n_rot; e += 256) {
+  for (int e = threadIdx.x; e < n_rot; e += 1024) {
     const int head = e / half, i = e % half;
     const int c1 = head * d + i, c2 = c1 + half;
     float x1 = 0.f, x2 = 0.f;
@@ -98,7 +109,7 @@ __global__ __launch_bounds__(256) void k_rope_kvwrite(const float* __restrict__ 
   }
   const int n_v = Hkv * d;
   const int voff = (Hq + Hkv) * d;
-  for (int e = threadIdx.x; e < n_v; e += 256) {
+  for (int e = threadIdx.x; e < n_v; e += 1024) {
     const int kvh = e / d, dim = e % d;
     float x = 0.f;
     for (int s = 0; s < S; ++s) x += src[(size_t)s * part_stride + voff + e];
@@ -106,22 +117,6 @@ __global__ __launch_bounds__(256) void k_rope_kvwrite(const float* __restrict__ 
     uint16_t* blk = (uint16_t*)(pool + ((size_t)pg * Hkv + kvh) * 2 * kbytes);
     blk[kbytes / 2 + ((size_t)(tk >> 3) * d + dim) * 8 + (tk & 7)] = f2bf(x);
   }
-}
-
-// act[r][32*b + i] = silu(g) * u with g = sum_s part[s][r][64*b + i], u = sum_s part[s][r][64*b + 32 + i]
-// (gate and up rows are interleaved in blocks of 32 in the fused weight).
-__global__ __launch_bounds__(256) void k_silu_mul(const float* __restrict__ part, int S, size_t part_stride,
-                                                  uint16_t* __restrict__ act, int F) {
-  const int r = blockIdx.y;
-  const int f = blockIdx.x * 256 + threadIdx.x;
-  if (f >= F) return;
-  const size_t c = (size_t)r * 2 * F + (size_t)(f >> 5) * 64 + (f & 31);
-  float g = 0.f, u = 0.f;
-  for (int s = 0; s < S; ++s) {
-    g += part[(size_t)s * part_stride + c];
-    u += part[(size_t)s * part_stride + c + 32];
-  }
-  act[(size_t)r * F + f] = f2bf(g / (1.0f + __expf(-g)) * u);
 }
 
 // Per row of fp32 logits: arg-max (lowest index on ties) and log-sum-exp.
@@ -185,6 +180,27 @@ __global__ __launch_bounds__(256) void k_repack(const void* __restrict__ src, in
   }
 }
 
+// Plain streaming kernels used to calibrate the memory counters and to measure the practical HBM ceiling.
+__global__ __launch_bounds__(256) void k_stream_copy(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+__global__ __launch_bounds__(256) void k_stream_read(const uint4* __restrict__ src, size_t n16, uint32_t* __restrict__ sink) {
+  uint32_t acc = 0;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) {
+    const uint4 v = src[i];
+    acc ^= v.x ^ v.y ^ v.z ^ v.w;
+  }
+  if (acc == 0x9E3779B9u) sink[0] = acc;   // practically never taken; keeps the loads alive
+}
+void launch_stream_copy(const void* src, void* dst, size_t bytes, hipStream_t st) {
+  const size_t n16 = bytes / 16;
+  if (n16) hipLaunchKernelGGL(k_stream_copy, dim3(256 * 16), dim3(256), 0, st, (const uint4*)src, (uint4*)dst, n16);
+}
+void launch_stream_read(const void* src, size_t bytes, void* sink, hipStream_t st) {
+  const size_t n16 = bytes / 16;
+  if (n16) hipLaunchKernelGGL(k_stream_read, dim3(256 * 16), dim3(256), 0, st, (const uint4*)src, n16, (uint32_t*)sink);
+}
+
 // ---------------------------------------------------------------------------------------------------
 void launch_repack(const void* src, int src_fp32, void* dst, int dst_fp32, size_t rows, size_t cols, size_t row0,
                    size_t blk, size_t blk_stride, hipStream_t st) {
@@ -201,18 +217,14 @@ void launch_embed(const void* table, const int* row_tok, float* h, int R, int D,
 void launch_add_rmsnorm(float* h, const float* part, int S, size_t part_stride, const float* gain, float eps, void* x,
                         int R, int D, hipStream_t st) {
   if (R > 0)
-    hipLaunchKernelGGL(k_add_rmsnorm, dim3(R), dim3(256), 0, st, h, part, S, part_stride, gain, eps, (uint16_t*)x, D);
+    hipLaunchKernelGGL(k_add_rmsnorm, dim3(R), dim3(1024), 0, st, h, part, S, part_stride, gain, eps, (uint16_t*)x, D);
 }
 void launch_rope_kvwrite(const float* part, int S, size_t part_stride, const float* bias, const int* row_slot,
                          const int* row_pos, const void* cs_table, void* q_out, void* pool, const int* page_table,
                          int max_pages, int Hq, int Hkv, int d, int R, hipStream_t st) {
   if (R > 0)
-    hipLaunchKernelGGL(k_rope_kvwrite, dim3(R), dim3(256), 0, st, part, S, part_stride, bias, row_slot, row_pos,
+    hipLaunchKernelGGL(k_rope_kvwrite, dim3(R), dim3(1024), 0, st, part, S, part_stride, bias, row_slot, row_pos,
                        (const float2*)cs_table, (uint16_t*)q_out, (uint8_t*)pool, page_table, max_pages, Hq, Hkv, d);
-}
-void launch_silu_mul(const float* part, int S, size_t part_stride, void* act, int R, int F, hipStream_t st) {
-  if (R > 0)
-    hipLaunchKernelGGL(k_silu_mul, dim3((F + 255) / 256, R), dim3(256), 0, st, part, S, part_stride, (uint16_t*)act, F);
 }
 void launch_argmax_lse(const float* logits, int V, int* row_argmax, float* row_lse, int R, hipStream_t st) {
   if (R > 0) hipLaunchKernelGGL(k_argmax_lse, dim3(R), dim3(1024), 0, st, logits, V, row_argmax, row_lse);

@@ -221,8 +221,8 @@ int load_weights(rollout_ctx* c, const void* weights, size_t weights_bytes) {
     }
     TRY(br.take(D, qd, L.wo, 0, 0, 0, 0));
     TRY(br.take(1, D, L.ffn_norm, 1, 0, 0, 0));
-    TRY(br.take(F, D, L.wgu, 0, 0, 32, 64));    // gate rows -> blocks 0,2,4,.. of 32
-    TRY(br.take(F, D, L.wgu, 0, 32, 32, 64));   // up rows   -> blocks 1,3,5,..
+    TRY(br.take(F, D, L.wgu, 0, 0, 16, 32));    // gate rows -> blocks 0,2,4,.. of 16
+    TRY(br.take(F, D, L.wgu, 0, 16, 16, 32));   // up rows   -> blocks 1,3,5,..
     TRY(br.take(D, F, L.wdown, 0, 0, 0, 0));
   }
   TRY(br.take(1, D, c->final_norm, 1, 0, 0, 0));
@@ -240,8 +240,7 @@ void run_layers(rollout_ctx* c, int R, const int* row_slot, const int* row_pos, 
   const float eps = c->cfg.rms_eps;
   launch_embed(c->embed, row_tok, c->h, R, D, st);
   launch_add_rmsnorm(c->h, nullptr, 0, 0, c->layers[0].attn_norm, eps, c->x, R, D, st);
-  const int S1 = gemm_pick_splits(R, Nqkv, D), S2 = gemm_pick_splits(R, D, Hq * d), S3 = gemm_pick_splits(R, 2 * F, D),
-            S4 = gemm_pick_splits(R, D, F);
+  const int S1 = gemm_pick_splits(R, Nqkv, D), S2 = gemm_pick_splits(R, D, Hq * d), S4 = gemm_pick_splits(R, D, F);
   for (int l = 0; l < c->NL; ++l) {
     const LayerW& L = c->layers[l];
     uint8_t* pool_l = c->kv_pool + (size_t)l * c->layer_pool_bytes;
@@ -268,14 +267,11 @@ void run_layers(rollout_ctx* c, int R, const int* row_slot, const int* row_pos, 
     if (n_tiles > 0) {
       launch_prefill_attn(pool_l, c->qbuf, pf_tiles, n_tiles, c->sd.page_table, c->max_pages, Hq, Hkv, d, c->attn_out, st);
     } else {
-      if (time_attn) (void)hipEventRecord(c->ev[2 * l], st);
-      launch_decode_attn(a, d, c->G, st);
-      if (time_attn) (void)hipEventRecord(c->ev[2 * l + 1], st);
+      launch_decode_attn(a, d, c->G, st, time_attn ? c->ev[2 * l] : nullptr, time_attn ? c->ev[2 * l + 1] : nullptr);
     }
     launch_gemm(c->attn_out, L.wo, c->part, R, D, Hq * d, S2, st);
     launch_add_rmsnorm(c->h, c->part, S2, (size_t)R * D, L.ffn_norm, eps, c->x, R, D, st);
-    launch_gemm(c->x, L.wgu, c->part, R, 2 * F, D, S3, st);
-    launch_silu_mul(c->part, S3, (size_t)R * 2 * F, c->act, R, F, st);
+    launch_gemm_swiglu(c->x, L.wgu, c->act, R, 2 * F, D, st);
     launch_gemm(c->act, L.wdown, c->part, R, D, F, S4, st);
     const float* next_gain = l + 1 < c->NL ? c->layers[l + 1].attn_norm : c->final_norm;
     launch_add_rmsnorm(c->h, c->part, S4, (size_t)R * D, next_gain, eps, c->x, R, D, st);
@@ -543,7 +539,6 @@ int rollout_init(rollout_ctx** out, const void* weights, size_t weights_bytes, c
       const int r = (int)rows;
       part_elems = std::max(part_elems, (size_t)gemm_pick_splits(r, c->Nqkv, c->D) * rows * c->Nqkv);
       part_elems = std::max(part_elems, (size_t)gemm_pick_splits(r, c->D, c->Hq * c->d) * rows * D);
-      part_elems = std::max(part_elems, (size_t)gemm_pick_splits(r, 2 * c->F, c->D) * rows * 2 * F);
       part_elems = std::max(part_elems, (size_t)gemm_pick_splits(r, c->D, c->F) * rows * D);
     }
     INIT_TRY(dev_alloc(c, &c->part, part_elems));
@@ -897,6 +892,18 @@ int rollout_attn_decode(const void* pool_dev, uint32_t n_q_heads, uint32_t n_kv_
   a.out_fp32 = out_fp32;
   a.need_merge = n_work > n;
   launch_decode_attn(a, (int)head_dim, (int)(n_q_heads / n_kv_heads), (hipStream_t)stream);
+  return hipGetLastError() == hipSuccess ? ROLLOUT_OK : fail(nullptr, ROLLOUT_EDEVICE, "kernel launch failed");
+}
+
+// ---- plain streaming kernels ---------------------------------------------------------------------------------
+int rollout_stream_copy(const void* src_dev, void* dst_dev, uint64_t bytes, void* stream) {
+  if (!src_dev || !dst_dev || bytes % 16) return fail(nullptr, ROLLOUT_EINVAL, "null pointer or size not a multiple of 16");
+  launch_stream_copy(src_dev, dst_dev, (size_t)bytes, (hipStream_t)stream);
+  return hipGetLastError() == hipSuccess ? ROLLOUT_OK : fail(nullptr, ROLLOUT_EDEVICE, "kernel launch failed");
+}
+int rollout_stream_read(const void* src_dev, uint64_t bytes, void* sink_dev, void* stream) {
+  if (!src_dev || !sink_dev || bytes % 16) return fail(nullptr, ROLLOUT_EINVAL, "null pointer or size not a multiple of 16");
+  launch_stream_read(src_dev, (size_t)bytes, sink_dev, (hipStream_t)stream);
   return hipGetLastError() == hipSuccess ? ROLLOUT_OK : fail(nullptr, ROLLOUT_EDEVICE, "kernel launch failed");
 }
 

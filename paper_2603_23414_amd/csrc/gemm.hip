@@ -18,7 +18,11 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // One k-step pairs MFMA k index (lane/32)*8 + e with memory k = (lane/32)*32 + j*8 + e inside the 64-wide block,
 // for A and W alike, so that every lane's four W loads of a block are 64 contiguous bytes (a row's two lanes
 // cover a whole 128-byte line per block).
-template <int MI>
+// EPI = 0: fp32 store of the (partial) sums.  EPI = 1: the SwiGLU epilogue -- W holds gate and up rows interleaved
+// in blocks of 16 (cols 32q..32q+15 = gate of features 16q.., cols 32q+16..32q+31 = up of the same features), the
+// two halves of a wave's 32 columns meet through one cross-lane exchange, and bf16 silu(gate)*up goes to
+// act[M, N/2].  No split-K in that mode.
+template <int MI, int EPI>
 __global__ __launch_bounds__(256, 2) void k_gemm_bf16(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
                                                       float* __restrict__ C, int M, int N, int K, int kb_per_split) {
   constexpr int BM = 32 * MI;
@@ -99,7 +103,21 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16(const uint16_t* __restrict
 
   // C fragment: element j of lane -> row (j/4)*8 + (lane/32)*4 + j%4, col lane%32
   const int n_out = n_base + (lane & 31);
-  if (n_out < N) {
+  if (EPI == 1) {
+    uint16_t* __restrict__ act = (uint16_t*)C;
+    const int F = N >> 1;
+    const int f_out = (n_base >> 1) + (lane & 15);
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const float mine = acc[i][j];
+        const float other = __shfl_xor(mine, 16, 64);     // gate lanes (bit 4 clear) receive the up value
+        const int mrow = m_base + i * 32 + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
+        if ((lane & 16) == 0 && mrow < M && n_out < N)
+          act[(size_t)mrow * F + f_out] = f2bf(mine / (1.0f + __expf(-mine)) * other);
+      }
+  } else if (n_out < N) {
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -132,20 +150,29 @@ int gemm_pick_splits(int M, int N, int K) {
   return (nkb + per - 1) / per;
 }
 
-void launch_gemm(const void* A, const void* W, float* C, int M, int N, int K, int S, hipStream_t st) {
-  if (M <= 0) return;
+template <int EPI>
+static void launch_gemm_t(const uint16_t* a, const uint16_t* w, float* C, int M, int N, int K, int S, hipStream_t st) {
   const int nkb = K / GEMM_BK;
   const int per = (nkb + S - 1) / S;
   const int mi = M <= 32 ? 1 : M <= 64 ? 2 : M <= 128 ? 4 : 8;
   dim3 grid((N + 127) / 128, (M + 32 * mi - 1) / (32 * mi), S);
-  const uint16_t* a = (const uint16_t*)A;
-  const uint16_t* w = (const uint16_t*)W;
   switch (mi) {
-    case 1: hipLaunchKernelGGL((k_gemm_bf16<1>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
-    case 2: hipLaunchKernelGGL((k_gemm_bf16<2>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
-    case 4: hipLaunchKernelGGL((k_gemm_bf16<4>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
-    default: hipLaunchKernelGGL((k_gemm_bf16<8>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
+    case 1: hipLaunchKernelGGL((k_gemm_bf16<1, EPI>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
+    case 2: hipLaunchKernelGGL((k_gemm_bf16<2, EPI>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
+    case 4: hipLaunchKernelGGL((k_gemm_bf16<4, EPI>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
+    default: hipLaunchKernelGGL((k_gemm_bf16<8, EPI>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
   }
+}
+
+void launch_gemm(const void* A, const void* W, float* C, int M, int N, int K, int S, hipStream_t st) {
+  if (M <= 0) return;
+  launch_gemm_t<0>((const uint16_t*)A, (const uint16_t*)W, C, M, N, K, S, st);
+}
+
+// act[M, N/2] (bf16) = silu(A Wg^T) * (A Wu^T) with Wg / Wu interleaved in W as described at the kernel.
+void launch_gemm_swiglu(const void* A, const void* W, void* act, int M, int N, int K, hipStream_t st) {
+  if (M <= 0) return;
+  launch_gemm_t<1>((const uint16_t*)A, (const uint16_t*)W, (float*)act, M, N, K, 1, st);
 }
 
 void launch_reduce_splits(const float* part, float* c, size_t mn, int S, hipStream_t st) {

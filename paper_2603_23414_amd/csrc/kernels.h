@@ -23,7 +23,8 @@ struct AttnArgs {
 };
 int attn_supported(int head_dim, int group);
 void launch_attn_worklist(const int* row_pos, int n_rows, int2* work, int* row_wstart, int* n_work_out, hipStream_t st);
-void launch_decode_attn(const AttnArgs& a, int head_dim, int group, hipStream_t st);
+void launch_decode_attn(const AttnArgs& a, int head_dim, int group, hipStream_t st, hipEvent_t ev0 = nullptr,
+                        hipEvent_t ev1 = nullptr);
 void launch_write_kv(void* pool, int Hkv, int head_dim, const void* k, const void* v, const int* tok_seq,
                      const int* tok_pos, const int* page_table, int max_pages, size_t n_tok, hipStream_t st);
 
@@ -35,6 +36,7 @@ void launch_prefill_attn(const void* pool, const void* q, const void* tiles, int
 // ---- GEMM ---------------------------------------------------------------------------------------------
 int gemm_pick_splits(int M, int N, int K);
 void launch_gemm(const void* A, const void* W, float* C, int M, int N, int K, int S, hipStream_t st);
+void launch_gemm_swiglu(const void* A, const void* W, void* act, int M, int N, int K, hipStream_t st);
 void launch_reduce_splits(const float* part, float* c, size_t mn, int S, hipStream_t st);
 
 // ---- fused small kernels ------------------------------------------------------------------------------
@@ -44,7 +46,6 @@ void launch_add_rmsnorm(float* h, const float* part, int S, size_t part_stride, 
 void launch_rope_kvwrite(const float* part, int S, size_t part_stride, const float* bias, const int* row_slot,
                          const int* row_pos, const void* cs_table, void* q_out, void* pool, const int* page_table,
                          int max_pages, int Hq, int Hkv, int d, int R, hipStream_t st);
-void launch_silu_mul(const float* part, int S, size_t part_stride, void* act, int R, int F, hipStream_t st);
 void launch_argmax_lse(const float* logits, int V, int* row_argmax, float* row_lse, int R, hipStream_t st);
 void launch_gather_rows(const float* src, const int* src_row, float* dst, int dst_row0, int n, int D, hipStream_t st);
 
@@ -98,3 +99,7 @@ void launch_prefill_rows(const SchedDev& d, const PrefillDesc* descs, int n_desc
 // weight repacking at init: dst[dst_row(r)][c] = convert(src[r][c]), dst_row(r) = row0 + (r / blk) * blk_stride + r % blk
 void launch_repack(const void* src, int src_fp32, void* dst, int dst_fp32, size_t rows, size_t cols, size_t row0,
                    size_t blk, size_t blk_stride, hipStream_t st);
+
+// plain streaming kernels (counter calibration, measured HBM ceiling)
+void launch_stream_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
+void launch_stream_read(const void* src, size_t bytes, void* sink, hipStream_t st);
