@@ -193,10 +193,15 @@ int rollout_attn_decode(const void* pool_dev, uint32_t n_q_heads, uint32_t n_kv_
                         const void* q_dev, const int32_t* page_table_dev, uint32_t max_pages, uint32_t n,
                         uint32_t n_work, void* out_dev, int out_fp32, void* workspace_dev, void* stream);
 
-/* ---- the bf16 MFMA projection GEMM alone: c[M,N] (fp32) = a[M,K] (bf16) * w[N,K]^T (bf16) ----
- * K must be a multiple of 64.  workspace_dev needs rollout_gemm_workspace_bytes(M, N, K) bytes. */
+/* ---- the bf16 MFMA projection GEMM alone: c[M,N] (fp32) = a[M,K] (bf16, row-major) * w[N,K]^T (bf16) ----
+ * The kernels read w in a packed fragment layout (tiles of 32 rows x 64 columns stored in the order the MFMA
+ * operand loads consume them, rows padded to a multiple of 32); rollout_gemm_pack_weights converts a row-major
+ * [N, K] matrix into rollout_gemm_packed_bytes(N, K) bytes at packed_dev.  K must be a multiple of 64.
+ * workspace_dev needs rollout_gemm_workspace_bytes(M, N, K) bytes.  All calls only enqueue on `stream`. */
+uint64_t rollout_gemm_packed_bytes(uint32_t N, uint32_t K);
+int rollout_gemm_pack_weights(const void* w_dev, void* packed_dev, uint32_t N, uint32_t K, void* stream);
 uint64_t rollout_gemm_workspace_bytes(uint32_t M, uint32_t N, uint32_t K);
-int rollout_gemm_bf16(const void* a_dev, const void* w_dev, float* c_dev, uint32_t M, uint32_t N, uint32_t K,
+int rollout_gemm_bf16(const void* a_dev, const void* w_packed_dev, float* c_dev, uint32_t M, uint32_t N, uint32_t K,
                       void* workspace_dev, uint64_t workspace_bytes, void* stream);
 
 /* ---- plain streaming kernels: dst = src, and a pure read of src (16-byte accesses, grid-stride).  They exist to

@@ -16,7 +16,7 @@ __all__ = [
     "rollout_peek", "rollout_slot_pages", "rollout_destroy", "rollout_last_error",
     "rollout_attn_pool_bytes", "rollout_attn_write_kv", "rollout_attn_workspace_bytes", "rollout_attn_plan",
     "rollout_attn_decode", "rollout_gemm_workspace_bytes", "rollout_gemm_bf16", "rollout_stream_copy",
-    "rollout_stream_read", "make_cfg",
+    "rollout_stream_read", "rollout_gemm_packed_bytes", "rollout_gemm_pack_weights", "make_cfg",
     "ROLLOUT_FLUSH", "ROLLOUT_DEBUG_NO_MODEL", "ROLLOUT_DEBUG_TIME_ATTN", "ROLLOUT_MODE_PARTIAL",
     "ROLLOUT_MODE_ONPOLICY", "ROLLOUT_MODE_SYNC", "ROLLOUT_EOS_FORCED_ONLY", "ROLLOUT_EOS_NATURAL_OR_FORCED",
     "EXPORTS",
@@ -39,6 +39,7 @@ EXPORTS = [
     "rollout_peek", "rollout_slot_pages", "rollout_last_error", "rollout_destroy", "rollout_attn_pool_bytes",
     "rollout_attn_write_kv", "rollout_attn_workspace_bytes", "rollout_attn_plan", "rollout_attn_decode",
     "rollout_gemm_workspace_bytes", "rollout_gemm_bf16", "rollout_stream_copy", "rollout_stream_read",
+    "rollout_gemm_packed_bytes", "rollout_gemm_pack_weights",
 ]
 
 
@@ -104,6 +105,9 @@ lib.rollout_gemm_workspace_bytes.restype = _u64
 lib.rollout_gemm_bf16.argtypes = [_vp, _vp, _vp, _u32, _u32, _u32, _vp, _u64, _vp]
 
 
+lib.rollout_gemm_packed_bytes.argtypes = [_u32, _u32]
+lib.rollout_gemm_packed_bytes.restype = _u64
+lib.rollout_gemm_pack_weights.argtypes = [_vp, _vp, _u32, _u32, _vp]
 lib.rollout_stream_copy.argtypes = [_vp, _vp, _u64, _vp]
 lib.rollout_stream_read.argtypes = [_vp, _u64, _vp, _vp]
 
@@ -258,3 +262,11 @@ def rollout_stream_copy(src_dev, dst_dev, nbytes, stream=0) -> None:
 
 def rollout_stream_read(src_dev, nbytes, sink_dev, stream=0) -> None:
     _check(lib.rollout_stream_read(src_dev, nbytes, sink_dev, stream))
+
+
+def rollout_gemm_packed_bytes(N, K) -> int:
+    return lib.rollout_gemm_packed_bytes(N, K)
+
+
+def rollout_gemm_pack_weights(w_dev, packed_dev, N, K, stream=0) -> None:
+    _check(lib.rollout_gemm_pack_weights(w_dev, packed_dev, N, K, stream))

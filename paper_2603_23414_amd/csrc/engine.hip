@@ -173,6 +173,15 @@ struct BlobReader {
   size_t esz, off = 0, total;
   void* tmp = nullptr;  // device staging for host blobs
   size_t tmp_bytes = 0;
+  uint16_t* rowmajor = nullptr;  // device staging: a projection matrix assembled row-major before it is packed
+  // pack the assembled [n_rows, cols] matrix (rows padded with zeros to a multiple of 32) into dst
+  int pack(size_t n_rows, size_t cols, uint16_t* dst) {
+    const size_t n_pad = (n_rows + 31) / 32 * 32;
+    if (n_pad > n_rows) HIPCHK(c, hipMemsetAsync(rowmajor + n_rows * cols, 0, (n_pad - n_rows) * cols * 2, c->stream));
+    launch_pack_weights(rowmajor, dst, n_pad, cols, c->stream);
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    return 0;
+  }
   int take(size_t rows, size_t cols, void* dst, int dst_fp32, size_t row0, size_t blk, size_t blk_stride) {
     const size_t bytes = rows * cols * esz;
     if (off + bytes > total) return fail(c, ROLLOUT_EINVAL, "weights blob smaller than the configured shape");
@@ -190,28 +199,37 @@ struct BlobReader {
 
 int load_weights(rollout_ctx* c, const void* weights, size_t weights_bytes) {
   const size_t D = c->D, F = c->F, V = c->V, qd = (size_t)c->Hq * c->d, kvd = (size_t)c->Hkv * c->d;
+  const auto pad32 = [](size_t n) { return (n + 31) / 32 * 32; };
   BlobReader br{c, (const uint8_t*)weights, c->cfg.weight_dtype == 0 ? (size_t)4 : (size_t)2, 0, weights_bytes};
+  // staging must hold the largest assembled matrix (with its padded rows)
+  const size_t big = std::max({pad32(V) * D, 2 * F * D, pad32((size_t)c->Nqkv) * D, pad32(D) * qd, pad32(D) * F});
   if (!c->cfg.weights_on_device) {
-    br.tmp_bytes = std::max(V * D, F * D) * br.esz;
-    TRY(dev_alloc(c, (uint8_t**)&br.tmp, br.tmp_bytes));
+    br.tmp_bytes = big * br.esz;
+    if (hipMalloc(&br.tmp, br.tmp_bytes) != hipSuccess) return fail(c, ROLLOUT_ENOMEM, "hipMalloc failed (weight staging)");
   }
+  if (hipMalloc((void**)&br.rowmajor, big * 2) != hipSuccess) return fail(c, ROLLOUT_ENOMEM, "hipMalloc failed (weight staging)");
+  struct Guard {   // staging is only needed while loading
+    BlobReader& b;
+    ~Guard() { if (b.tmp) (void)hipFree(b.tmp); if (b.rowmajor) (void)hipFree(b.rowmajor); }
+  } guard{br};
   TRY(dev_alloc(c, &c->embed, V * D));
-  TRY(dev_alloc(c, &c->lm_head, V * D));
+  TRY(dev_alloc(c, &c->lm_head, pad32(V) * D));
   TRY(dev_alloc(c, &c->final_norm, D));
   TRY(br.take(V, D, c->embed, 0, 0, 0, 0));
   c->layers.resize(c->NL);
   for (int l = 0; l < c->NL; ++l) {
     LayerW& L = c->layers[l];
     TRY(dev_alloc(c, &L.attn_norm, D));
-    TRY(dev_alloc(c, &L.wqkv, (size_t)c->Nqkv * D));
-    TRY(dev_alloc(c, &L.wo, D * qd));
+    TRY(dev_alloc(c, &L.wqkv, pad32((size_t)c->Nqkv) * D));
+    TRY(dev_alloc(c, &L.wo, pad32(D) * qd));
     TRY(dev_alloc(c, &L.ffn_norm, D));
     TRY(dev_alloc(c, &L.wgu, 2 * F * D));
-    TRY(dev_alloc(c, &L.wdown, D * F));
+    TRY(dev_alloc(c, &L.wdown, pad32(D) * F));
     TRY(br.take(1, D, L.attn_norm, 1, 0, 0, 0));
-    TRY(br.take(qd, D, L.wqkv, 0, 0, 0, 0));
-    TRY(br.take(kvd, D, L.wqkv, 0, qd, 0, 0));
-    TRY(br.take(kvd, D, L.wqkv, 0, qd + kvd, 0, 0));
+    TRY(br.take(qd, D, br.rowmajor, 0, 0, 0, 0));
+    TRY(br.take(kvd, D, br.rowmajor, 0, qd, 0, 0));
+    TRY(br.take(kvd, D, br.rowmajor, 0, qd + kvd, 0, 0));
+    TRY(br.pack((size_t)c->Nqkv, D, L.wqkv));
     if (c->cfg.qkv_bias) {
       TRY(dev_alloc(c, &L.bqkv, (size_t)c->Nqkv));
       // biases are [1, n] rows in the blob: load them as n rows of one column so they land contiguously
@@ -219,14 +237,18 @@ int load_weights(rollout_ctx* c, const void* weights, size_t weights_bytes) {
       TRY(br.take(kvd, 1, L.bqkv, 1, qd, 0, 0));
       TRY(br.take(kvd, 1, L.bqkv, 1, qd + kvd, 0, 0));
     }
-    TRY(br.take(D, qd, L.wo, 0, 0, 0, 0));
+    TRY(br.take(D, qd, br.rowmajor, 0, 0, 0, 0));
+    TRY(br.pack(D, qd, L.wo));
     TRY(br.take(1, D, L.ffn_norm, 1, 0, 0, 0));
-    TRY(br.take(F, D, L.wgu, 0, 0, 16, 32));    // gate rows -> blocks 0,2,4,.. of 16
-    TRY(br.take(F, D, L.wgu, 0, 16, 16, 32));   // up rows   -> blocks 1,3,5,..
-    TRY(br.take(D, F, L.wdown, 0, 0, 0, 0));
+    TRY(br.take(F, D, br.rowmajor, 0, 0, 16, 32));    // gate rows -> blocks 0,2,4,.. of 16
+    TRY(br.take(F, D, br.rowmajor, 0, 16, 16, 32));   // up rows   -> blocks 1,3,5,..
+    TRY(br.pack(2 * F, D, L.wgu));
+    TRY(br.take(D, F, br.rowmajor, 0, 0, 0, 0));
+    TRY(br.pack(D, F, L.wdown));
   }
   TRY(br.take(1, D, c->final_norm, 1, 0, 0, 0));
-  TRY(br.take(V, D, c->lm_head, 0, 0, 0, 0));
+  TRY(br.take(V, D, br.rowmajor, 0, 0, 0, 0));
+  TRY(br.pack(V, D, c->lm_head));
   if (br.off != weights_bytes) return fail(c, ROLLOUT_EINVAL, "weights blob larger than the configured shape");
   HIPCHK(c, hipStreamSynchronize(c->stream));
   return 0;
@@ -908,19 +930,31 @@ int rollout_stream_read(const void* src_dev, uint64_t bytes, void* sink_dev, voi
 }
 
 // ---- standalone GEMM ---------------------------------------------------------------------------------------
+uint64_t rollout_gemm_packed_bytes(uint32_t N, uint32_t K) { return (uint64_t)((N + 31) / 32 * 32) * K * 2ull; }
+int rollout_gemm_pack_weights(const void* w_dev, void* packed_dev, uint32_t N, uint32_t K, void* stream) {
+  if (!w_dev || !packed_dev || N == 0 || K == 0) return fail(nullptr, ROLLOUT_EINVAL, "null argument");
+  if (K % 64) return fail(nullptr, ROLLOUT_EINVAL, "K must be a multiple of 64");
+  const uint32_t n_pad = (N + 31) / 32 * 32;
+  if (n_pad > N) {   // rows past N inside the last tile: zero them, then pack the N real rows
+    if (hipMemsetAsync((uint8_t*)packed_dev + (size_t)(N / 32) * 32 * K * 2, 0, (size_t)32 * K * 2, (hipStream_t)stream) != hipSuccess)
+      return fail(nullptr, ROLLOUT_EDEVICE, "hipMemsetAsync failed");
+  }
+  launch_pack_weights(w_dev, packed_dev, N, K, (hipStream_t)stream);
+  return hipGetLastError() == hipSuccess ? ROLLOUT_OK : fail(nullptr, ROLLOUT_EDEVICE, "kernel launch failed");
+}
 uint64_t rollout_gemm_workspace_bytes(uint32_t M, uint32_t N, uint32_t K) {
   return (uint64_t)gemm_pick_splits((int)M, (int)N, (int)K) * M * N * 4ull + 256;
 }
-int rollout_gemm_bf16(const void* a_dev, const void* w_dev, float* c_dev, uint32_t M, uint32_t N, uint32_t K,
+int rollout_gemm_bf16(const void* a_dev, const void* w_packed_dev, float* c_dev, uint32_t M, uint32_t N, uint32_t K,
                       void* workspace_dev, uint64_t workspace_bytes, void* stream) {
-  if (!a_dev || !w_dev || !c_dev || M == 0 || N == 0 || K == 0) return fail(nullptr, ROLLOUT_EINVAL, "null argument");
+  if (!a_dev || !w_packed_dev || !c_dev || M == 0 || N == 0 || K == 0) return fail(nullptr, ROLLOUT_EINVAL, "null argument");
   if (K % 64) return fail(nullptr, ROLLOUT_EINVAL, "K must be a multiple of 64");
   const int S = gemm_pick_splits((int)M, (int)N, (int)K);
   if (S == 1) {
-    launch_gemm(a_dev, w_dev, c_dev, (int)M, (int)N, (int)K, 1, (hipStream_t)stream);
+    launch_gemm(a_dev, w_packed_dev, c_dev, (int)M, (int)N, (int)K, 1, (hipStream_t)stream);
   } else {
     if (!workspace_dev || workspace_bytes < (uint64_t)S * M * N * 4ull) return fail(nullptr, ROLLOUT_EINVAL, "workspace too small");
-    launch_gemm(a_dev, w_dev, (float*)workspace_dev, (int)M, (int)N, (int)K, S, (hipStream_t)stream);
+    launch_gemm(a_dev, w_packed_dev, (float*)workspace_dev, (int)M, (int)N, (int)K, S, (hipStream_t)stream);
     launch_reduce_splits((const float*)workspace_dev, c_dev, (size_t)M * N, S, (hipStream_t)stream);
   }
   return hipGetLastError() == hipSuccess ? ROLLOUT_OK : fail(nullptr, ROLLOUT_EDEVICE, "kernel launch failed");

@@ -13,6 +13,13 @@
 
 #define GEMM_BK 64
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Packed weight layout ("W fragments"): the matrix is cut into tiles of 32 rows (n) x 64 columns (k); tile
+// (nt, kb) holds 4 k-steps x 64 lanes x 8 bf16, lane l of k-step j carrying W[nt*32 + l%32][kb*64 + (l/32)*32 + j*8 .. +8].
+// A wavefront's 16-byte-per-lane load of one k-step is then one contiguous KiB (fully coalesced), where the same
+// fragment read from a row-major matrix touches 32 different rows; that was the decode GEMM's real limit (address
+// processing in the texture path, not HBM, LDS or MFMA).  Rows are padded with zeros to a multiple of 32.
+#define WTILE_ELEMS 2048   // bf16 elements per (nt, kb) tile
 #define LDS_ROW 72   // bf16 elements per LDS row: 64 + 8 padding (144-byte stride: conflict-free 16-byte reads)
 
 // One k-step pairs MFMA k index (lane/32)*8 + e with memory k = (lane/32)*32 + j*8 + e inside the 64-wide block,
@@ -36,8 +43,8 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16(const uint16_t* __restrict
   const int nkb = min(kb_per_split, nkb_total - kb0);
   float* __restrict__ Cz = C + (size_t)blockIdx.z * M * N;
 
-  const int n_lane = min(n_base + (lane & 31), N - 1);
-  const uint16_t* __restrict__ wrow = W + (size_t)n_lane * K + (size_t)kb0 * GEMM_BK + (lane >> 5) * 32;
+  const int nt = min(n_base, N - 1) >> 5;                      // this wave's 32-row weight tile (clamped past the edge)
+  const uint16_t* __restrict__ wrow = W + ((size_t)nt * nkb_total + kb0) * WTILE_ELEMS + lane * 8;
 
   const int a_col = tid & 7;
   const uint16_t* a_src[MI];
@@ -61,11 +68,11 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16(const uint16_t* __restrict
 #pragma unroll
   for (int i = 0; i < MI; ++i) areg[i] = *(const u32x4*)(a_src[i]);
 #pragma unroll
-  for (int j = 0; j < 4; ++j) breg[0][j] = *(const u32x4*)(wrow + j * 8);
+  for (int j = 0; j < 4; ++j) breg[0][j] = *(const u32x4*)(wrow + j * 512);
   {
-    const size_t k1 = (size_t)min(1, nkb - 1) * GEMM_BK;
+    const size_t w1 = (size_t)min(1, nkb - 1) * WTILE_ELEMS;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) breg[1][j] = *(const u32x4*)(wrow + k1 + j * 8);
+    for (int j = 0; j < 4; ++j) breg[1][j] = *(const u32x4*)(wrow + w1 + j * 512);
   }
 #pragma unroll
   for (int i = 0; i < MI; ++i) *(u32x4*)&a_lds[0][a_dst[i]] = areg[i];
@@ -79,11 +86,12 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16(const uint16_t* __restrict
         const int cur = kb & 1;
         // prefetch: A one block ahead (to registers, then LDS), W two blocks ahead (register ring).  Past the
         // end the last block is simply loaded again, which keeps the loop free of conditional register writes.
-        const size_t k1 = (size_t)min(kb + 1, nkb - 1) * GEMM_BK, k2 = (size_t)min(kb + 2, nkb - 1) * GEMM_BK;
+        const size_t k1 = (size_t)min(kb + 1, nkb - 1) * GEMM_BK, w2 = (size_t)min(kb + 2, nkb - 1) * WTILE_ELEMS;
 #pragma unroll
         for (int i = 0; i < MI; ++i) areg[i] = *(const u32x4*)(a_src[i] + k1);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) breg[(u + 2) % 3][j] = *(const u32x4*)(wrow + k2 + j * 8);
+        for (int j = 0; j < 4; ++j) breg[(u + 2) % 3][j] = *(const u32x4*)(wrow + w2 + j * 512);
+        __builtin_amdgcn_sched_barrier(0);   // keep the prefetch loads ahead of this block's MFMAs
         const uint16_t* al = a_lds[cur] + a_frag;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -128,6 +136,161 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16(const uint16_t* __restrict
   }
 }
 
+// Variant for launches that cannot fill the chip twice over (<= ~1 workgroup per CU, i.e. every decode projection
+// except the LM head): one workgroup per CU gets the whole register file (accumulators move to AGPRs), the W ring
+// is 4 blocks deep, A staging runs two blocks ahead, and the A fragments of a k-step are all fetched from LDS before
+// its MFMAs issue and double-buffered across k-steps -- with a single wave per SIMD nothing else could hide those
+// latencies.  A wave owns MIW x NJ MFMA tiles; 8 x 1 (256 rows x 32 columns) is what is launched.  4 x 2 (an A
+// fragment feeds two MFMAs, half the LDS reads, W fragments fetched by two waves) measured 5-8 % slower at M = 256.
+template <int MIW, int NJ, int EPI>
+__global__ __launch_bounds__(256, 1) void k_gemm_bf16_deep(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
+                                                           float* __restrict__ C, int M, int N, int K, int kb_per_split) {
+  constexpr int BM = 256;
+  constexpr int WM = 8 / MIW;          // waves along M
+  __shared__ __align__(16) uint16_t a_lds[2][BM * LDS_ROW];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = w % WM, wn = w / WM;
+  const int n_base = blockIdx.x * 128 + wn * (32 * NJ);
+  const int m_base = blockIdx.y * BM;
+  const int nkb_total = K / GEMM_BK;
+  const int kb0 = blockIdx.z * kb_per_split;
+  const int nkb = min(kb_per_split, nkb_total - kb0);
+  float* __restrict__ Cz = C + (size_t)blockIdx.z * M * N;
+  const uint16_t* wrow[NJ];
+#pragma unroll
+  for (int t = 0; t < NJ; ++t)
+    wrow[t] = W + ((size_t)(min(n_base + t * 32, N - 1) >> 5) * nkb_total + kb0) * WTILE_ELEMS + lane * 8;
+  const int a_col = tid & 7;
+  const uint16_t* a_src[8];
+  int a_dst[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int r = (tid >> 3) + i * 32;
+    a_src[i] = A + (size_t)min(m_base + r, M - 1) * K + (size_t)kb0 * GEMM_BK + a_col * 8;
+    a_dst[i] = r * LDS_ROW + a_col * 8;
+  }
+  const int a_frag = (wm * (32 * MIW) + (lane & 31)) * LDS_ROW + (lane >> 5) * 32;
+
+  f32x16_t acc[MIW][NJ];
+#pragma unroll
+  for (int i = 0; i < MIW; ++i)
+#pragma unroll
+    for (int t = 0; t < NJ; ++t)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) acc[i][t][j] = 0.f;
+
+  u32x4 breg[4][NJ][4];  // W ring: block kb + 3 is in flight while block kb is multiplied
+  u32x4 areg[2][8];      // A staging: block kb + 2 is in flight, block kb + 1 goes to LDS at the end of block kb
+  u32x4 af[2][MIW];      // A fragments of the current and the next k-step
+#pragma unroll
+  for (int i = 0; i < 8; ++i) areg[0][i] = *(const u32x4*)(a_src[i]);
+  {
+    const size_t k1 = (size_t)min(1, nkb - 1) * GEMM_BK;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) areg[1][i] = *(const u32x4*)(a_src[i] + k1);
+  }
+#pragma unroll
+  for (int r = 0; r < 3; ++r) {
+    const size_t wr = (size_t)min(r, nkb - 1) * WTILE_ELEMS;
+#pragma unroll
+    for (int t = 0; t < NJ; ++t)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) breg[r][t][j] = *(const u32x4*)(wrow[t] + wr + j * 512);
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) *(u32x4*)&a_lds[0][a_dst[i]] = areg[0][i];
+  __syncthreads();
+
+  for (int kbase = 0; kbase < nkb; kbase += 4) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int kb = kbase + u;
+      if (kb < nkb) {                                    // uniform
+        const int cur = kb & 1;
+        const size_t k2 = (size_t)min(kb + 2, nkb - 1) * GEMM_BK, w3 = (size_t)min(kb + 3, nkb - 1) * WTILE_ELEMS;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) areg[u & 1][i] = *(const u32x4*)(a_src[i] + k2);
+#pragma unroll
+        for (int t = 0; t < NJ; ++t)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) breg[(u + 3) & 3][t][j] = *(const u32x4*)(wrow[t] + w3 + j * 512);
+        const uint16_t* al = a_lds[cur] + a_frag;
+#pragma unroll
+        for (int i = 0; i < MIW; ++i) af[0][i] = *(const u32x4*)(al + i * 32 * LDS_ROW);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if (j < 3) {
+#pragma unroll
+            for (int i = 0; i < MIW; ++i) af[(j + 1) & 1][i] = *(const u32x4*)(al + i * 32 * LDS_ROW + (j + 1) * 8);
+          }
+#pragma unroll
+          for (int t = 0; t < NJ; ++t) {
+            const bf16x8_t bf = __builtin_bit_cast(bf16x8_t, breg[u][t][j]);
+#pragma unroll
+            for (int i = 0; i < MIW; ++i)
+              acc[i][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af[j & 1][i]), bf,
+                                                                  acc[i][t], 0, 0, 0);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) *(u32x4*)&a_lds[cur ^ 1][a_dst[i]] = areg[(u + 1) & 1][i];
+        __syncthreads();
+      }
+    }
+  }
+
+#pragma unroll
+  for (int t = 0; t < NJ; ++t) {
+    const int n_out = n_base + t * 32 + (lane & 31);
+    if (EPI == 1) {
+      uint16_t* __restrict__ act = (uint16_t*)C;
+      const int F = N >> 1;
+      const int f_out = ((n_base + t * 32) >> 1) + (lane & 15);
+#pragma unroll
+      for (int i = 0; i < MIW; ++i)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          const float mine = acc[i][t][j];
+          const float other = __shfl_xor(mine, 16, 64);
+          const int mrow = m_base + wm * (32 * MIW) + i * 32 + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
+          if ((lane & 16) == 0 && mrow < M && n_out < N)
+            act[(size_t)mrow * F + f_out] = f2bf(mine / (1.0f + __expf(-mine)) * other);
+        }
+    } else if (n_out < N) {
+#pragma unroll
+      for (int i = 0; i < MIW; ++i)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          const int mrow = m_base + wm * (32 * MIW) + i * 32 + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
+          if (mrow < M) Cz[(size_t)mrow * N + n_out] = acc[i][t][j];
+        }
+    }
+  }
+}
+
+// Row-major [N, K] bf16 -> packed W fragments (rows padded to a multiple of 32 must be zeroed by the caller).
+__global__ __launch_bounds__(256) void k_pack_weights(const uint16_t* __restrict__ src, uint16_t* __restrict__ dst,
+                                                      size_t N, size_t K) {
+  const size_t total = N * K / 8;   // 16-byte groups
+  const size_t nkb = K / GEMM_BK;
+  for (size_t g = (size_t)blockIdx.x * 256 + threadIdx.x; g < total; g += (size_t)gridDim.x * 256) {
+    const size_t n = g / (K / 8), k = (g % (K / 8)) * 8;
+    const size_t kk = k % GEMM_BK;
+    const size_t lane = (kk / 32) * 32 + n % 32, j = (kk % 32) / 8;
+    const size_t o = ((n / 32) * nkb + k / GEMM_BK) * WTILE_ELEMS + j * 512 + lane * 8;
+    *(u32x4*)(dst + o) = *(const u32x4*)(src + n * K + k);
+  }
+}
+void launch_pack_weights(const void* src, void* dst, size_t N, size_t K, hipStream_t st) {
+  const size_t total = N * K / 8;
+  if (!total) return;
+  const unsigned blocks = (unsigned)((total + 255) / 256 < 262144 ? (total + 255) / 256 : 262144);
+  hipLaunchKernelGGL(k_pack_weights, dim3(blocks), dim3(256), 0, st, (const uint16_t*)src, (uint16_t*)dst, N, K);
+}
+
 __global__ void k_reduce_splits(const float* __restrict__ part, float* __restrict__ c, size_t mn, int S) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= mn) return;
@@ -156,6 +319,10 @@ static void launch_gemm_t(const uint16_t* a, const uint16_t* w, float* C, int M,
   const int per = (nkb + S - 1) / S;
   const int mi = M <= 32 ? 1 : M <= 64 ? 2 : M <= 128 ? 4 : 8;
   dim3 grid((N + 127) / 128, (M + 32 * mi - 1) / (32 * mi), S);
+  if (mi == 8 && (long long)grid.x * grid.y * grid.z <= 256) {   // at most one workgroup per CU: the deep variant
+    hipLaunchKernelGGL((k_gemm_bf16_deep<8, 1, EPI>), grid, dim3(256), 0, st, a, w, C, M, N, K, per);
+    return;
+  }
   switch (mi) {
     case 1: hipLaunchKernelGGL((k_gemm_bf16<1, EPI>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
     case 2: hipLaunchKernelGGL((k_gemm_bf16<2, EPI>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;

@@ -37,6 +37,8 @@ void launch_prefill_attn(const void* pool, const void* q, const void* tiles, int
 int gemm_pick_splits(int M, int N, int K);
 void launch_gemm(const void* A, const void* W, float* C, int M, int N, int K, int S, hipStream_t st);
 void launch_gemm_swiglu(const void* A, const void* W, void* act, int M, int N, int K, hipStream_t st);
+// row-major [N, K] -> the packed fragment layout the GEMM kernels read (N * K elements; N a multiple of 32)
+void launch_pack_weights(const void* src, void* dst, size_t N, size_t K, hipStream_t st);
 void launch_reduce_splits(const float* part, float* c, size_t mn, int S, hipStream_t st);
 
 // ---- fused small kernels ------------------------------------------------------------------------------

@@ -8,7 +8,9 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("M,N,K", [(1, 128, 64), (8, 384, 128), (33, 512, 512), (128, 6144, 4096), (256, 4096, 4096),
-                                   (250, 1000, 1024), (300, 256, 14336 // 7), (700, 640, 256), (64, 128256 // 4, 128)])
+                                   (250, 1000, 1024), (300, 256, 14336 // 7), (700, 640, 256), (64, 128256 // 4, 128),
+                                   (333, 384, 128), (333, 128, 128), (2, 256, 128), (437, 256, 64), (4096, 128, 128),
+                                   (256, 4096, 192)])
 def test_gemm_matches_float64(M, N, K):
     import torch
     import paper_2603_23414_amd as R
@@ -21,7 +23,9 @@ def test_gemm_matches_float64(M, N, K):
     c_d = torch.full((M, N), float("nan"), dtype=torch.float32, device=dev)
     ws_bytes = R.rollout_gemm_workspace_bytes(M, N, K)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
-    R.rollout_gemm_bf16(a_d.data_ptr(), w_d.data_ptr(), c_d.data_ptr(), M, N, K, ws.data_ptr(), ws_bytes)
+    wp = torch.full((R.rollout_gemm_packed_bytes(N, K) // 2,), 0x7FC0, dtype=torch.int16, device=dev)
+    R.rollout_gemm_pack_weights(w_d.data_ptr(), wp.data_ptr(), N, K)
+    R.rollout_gemm_bf16(a_d.data_ptr(), wp.data_ptr(), c_d.data_ptr(), M, N, K, ws.data_ptr(), ws_bytes)
     torch.cuda.synchronize()
     got = c_d.cpu().numpy().astype(np.float64)
     ref = W.bf16_bits_to_f32(a).astype(np.float64) @ W.bf16_bits_to_f32(w).astype(np.float64).T
