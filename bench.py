@@ -10,6 +10,7 @@ generated tokens (what partial mode re-feeds after an interruption); their prefi
 """
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -219,8 +220,12 @@ def main():
     prompts = [g.integers(0, m.vocab - 1, size=wl.prompt_len + gl, dtype=np.int64).astype(np.int32) for _, gl in order]
     targets = np.array([int(L[sid]) - gl for sid, gl in order], np.uint32)
     cap = int(targets.max())
+    # the warm start inflates max_prompt_len, so never let the library size the pool for the worst case: use the
+    # workload's pool, else the worst case of the ORIGINAL workload capped at 120 GB (the 32B weights need the rest)
+    page_bytes = wl.model.n_layers * wl.model.n_kv_heads * 2 * 16 * wl.model.head_dim * 2
+    pool_bytes = wl.kv_pool_bytes or min(120 * 10**9, wl.max_slots * ((wl.prompt_len + wl.cap + 15) // 16) * page_bytes)
     cfg = R.make_cfg(m, max_slots=wl.max_slots, max_prompt_len=max_prompt, max_new_tokens=cap, max_seqs=len(order),
-                     kv_pool_bytes=wl.kv_pool_bytes * m.n_layers // wl.model.n_layers, weights_on_device=1,
+                     kv_pool_bytes=pool_bytes * m.n_layers // wl.model.n_layers, weights_on_device=1,
                      max_staleness=wl.max_staleness, debug_flags=R.ROLLOUT_DEBUG_TIME_ATTN)
     ctx = R.rollout_init((blob.data_ptr(), blob.numel() * 2), cfg)
     del blob
@@ -263,12 +268,14 @@ def main():
                     traffic=None if args.layers else MEASURED_TRAFFIC_BYTES.get((wl.name, args.steps, args.warmup)),
                     launches=int(launches), avg_launch_ms=attn_ms / max(1, launches),
                     alg_bytes_per_launch=alg_bytes / max(1, launches))
-    out = dict(metric="rollout tokens/s (8B shape, 16k-cap lengths)", value=tokens / dt, unit="tokens/s", n_gpus=1,
+    out = dict(metric="rollout tokens/s (8B shape, 16k-cap lengths)" if wl.name == "8b_long" else f"rollout tokens/s ({wl.name})", value=tokens / dt, unit="tokens/s", n_gpus=1,
                steps=args.steps, warmup=args.warmup, ms_per_step=1e3 * dt / args.steps, higher_is_better=True,
                scaling="weak", vs_baseline=None, dtype="bf16", data="synthetic",
-               config=dict(workload=f"{wl.name}: LLaMA-3.1-8B shape ({m.n_layers} layers), Q={wl.max_slots}, "
-                                    f"{wl.n_prompts} prompts x {wl.prompt_len}, LogNormal(median 2048, sigma 1.0) cap "
-                                    f"{wl.cap}, KV pool {wl.kv_pool_bytes / 1e9:.0f} GB, harvest {wl.harvest}, "
+               config=dict(workload=f"{wl.name}: {'LLaMA-3.1-8B' if m.d_model == 4096 else 'Qwen-2.5-32B' if m.d_model == 5120 else 'tiny'} "
+                                    f"shape ({m.n_layers} layers), Q={wl.max_slots}, "
+                                    f"{wl.n_prompts} prompts x {wl.prompt_len}, LogNormal(median {math.exp(wl.len_mu):.0f}, "
+                                    f"sigma {wl.len_sigma}) cap {wl.cap}, KV pool "
+                                    f"{(str(round(wl.kv_pool_bytes / 1e9)) + ' GB') if wl.kv_pool_bytes else 'worst-case'}, harvest {wl.harvest}, "
                                     f"max_staleness {wl.max_staleness}; timed window from scheduler step "
                                     f"{snap['step']} (mean in-flight context)",
                            mean_inflight_ctx=snap["mean_ctx_sum"] / wl.max_slots,

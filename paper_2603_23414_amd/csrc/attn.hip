@@ -66,7 +66,7 @@ __global__ __launch_bounds__(256) void k_decode_attn(
     const uint8_t* kb = pool + ((size_t)pg * Hkv + kvh) * BLK + (tok & 15) * 16;
     uint4 kr[NCH];
 #pragma unroll
-    for (int c = 0; c < NCH; ++c) kr[c] = *(const uint4*)(kb + c * 256);
+    for (int c = 0; c < NCH; ++c) kr[c] = ld_stream16(kb + c * 256);
     uint4 vr[4][2][DPL];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -76,7 +76,7 @@ __global__ __launch_bounds__(256) void k_decode_attn(
 #pragma unroll
         for (int dd = 0; dd < DPL; ++dd) {
           const int dim = (D >= 64) ? lane + dd * 64 : (lane & (D - 1));
-          vr[j][half][dd] = *(const uint4*)(vb + ((size_t)half * D + dim) * 16);
+          vr[j][half][dd] = ld_stream16(vb + ((size_t)half * D + dim) * 16);
         }
     }
     // ---- scores -----------------------------------------------------------------------------------------

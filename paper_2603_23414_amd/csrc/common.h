@@ -36,5 +36,12 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
+// 16-byte streaming load: data that is read once per kernel (KV pages, weights) should not displace what is reused
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 ld_stream16(const void* p) {
+  const u32x4_t t = __builtin_nontemporal_load((const u32x4_t*)p);
+  return make_uint4(t.x, t.y, t.z, t.w);
+}
+
 // bytes of one (page, kv head) block: K then V, bf16
 __host__ __device__ __forceinline__ size_t kv_block_bytes(int head_dim) { return (size_t)2 * PAGE_TOKENS * head_dim * 2; }

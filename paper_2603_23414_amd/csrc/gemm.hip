@@ -20,6 +20,11 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // fragment read from a row-major matrix touches 32 different rows; that was the decode GEMM's real limit (address
 // processing in the texture path, not HBM, LDS or MFMA).  Rows are padded with zeros to a multiple of 32.
 #define WTILE_ELEMS 2048   // bf16 elements per (nt, kb) tile
+
+template <bool STREAM>
+__device__ __forceinline__ u32x4 ldw(const uint16_t* p) {
+  return STREAM ? __builtin_nontemporal_load((const u32x4*)p) : *(const u32x4*)p;
+}
 #define LDS_ROW 72   // bf16 elements per LDS row: 64 + 8 padding (144-byte stride: conflict-free 16-byte reads)
 
 // One k-step pairs MFMA k index (lane/32)*8 + e with memory k = (lane/32)*32 + j*8 + e inside the 64-wide block,
@@ -29,7 +34,9 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // in blocks of 16 (cols 32q..32q+15 = gate of features 16q.., cols 32q+16..32q+31 = up of the same features), the
 // two halves of a wave's 32 columns meet through one cross-lane exchange, and bf16 silu(gate)*up goes to
 // act[M, N/2].  No split-K in that mode.
-template <int MI, int EPI>
+// STREAM = true reads W with streaming (non-temporal) loads: right when every weight byte is used once per launch
+// (M <= 256), wrong when several row blocks re-read the same W slab from L2 (prefill).
+template <int MI, int EPI, bool STREAM>
 __global__ __launch_bounds__(256, 2) void k_gemm_bf16(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
                                                       float* __restrict__ C, int M, int N, int K, int kb_per_split) {
   constexpr int BM = 32 * MI;
@@ -68,11 +75,11 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16(const uint16_t* __restrict
 #pragma unroll
   for (int i = 0; i < MI; ++i) areg[i] = *(const u32x4*)(a_src[i]);
 #pragma unroll
-  for (int j = 0; j < 4; ++j) breg[0][j] = *(const u32x4*)(wrow + j * 512);
+  for (int j = 0; j < 4; ++j) breg[0][j] = ldw<STREAM>(wrow + j * 512);
   {
     const size_t w1 = (size_t)min(1, nkb - 1) * WTILE_ELEMS;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) breg[1][j] = *(const u32x4*)(wrow + w1 + j * 512);
+    for (int j = 0; j < 4; ++j) breg[1][j] = ldw<STREAM>(wrow + w1 + j * 512);
   }
 #pragma unroll
   for (int i = 0; i < MI; ++i) *(u32x4*)&a_lds[0][a_dst[i]] = areg[i];
@@ -90,7 +97,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16(const uint16_t* __restrict
 #pragma unroll
         for (int i = 0; i < MI; ++i) areg[i] = *(const u32x4*)(a_src[i] + k1);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) breg[(u + 2) % 3][j] = *(const u32x4*)(wrow + w2 + j * 512);
+        for (int j = 0; j < 4; ++j) breg[(u + 2) % 3][j] = ldw<STREAM>(wrow + w2 + j * 512);
         __builtin_amdgcn_sched_barrier(0);   // keep the prefetch loads ahead of this block's MFMAs
         const uint16_t* al = a_lds[cur] + a_frag;
 #pragma unroll
@@ -196,7 +203,7 @@ __global__ __launch_bounds__(256, 1) void k_gemm_bf16_deep(const uint16_t* __res
 #pragma unroll
     for (int t = 0; t < NJ; ++t)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) breg[r][t][j] = *(const u32x4*)(wrow[t] + wr + j * 512);
+      for (int j = 0; j < 4; ++j) breg[r][t][j] = __builtin_nontemporal_load((const u32x4*)(wrow[t] + wr + j * 512));
   }
 #pragma unroll
   for (int i = 0; i < 8; ++i) *(u32x4*)&a_lds[0][a_dst[i]] = areg[0][i];
@@ -214,7 +221,7 @@ __global__ __launch_bounds__(256, 1) void k_gemm_bf16_deep(const uint16_t* __res
 #pragma unroll
         for (int t = 0; t < NJ; ++t)
 #pragma unroll
-          for (int j = 0; j < 4; ++j) breg[(u + 3) & 3][t][j] = *(const u32x4*)(wrow[t] + w3 + j * 512);
+          for (int j = 0; j < 4; ++j) breg[(u + 3) & 3][t][j] = __builtin_nontemporal_load((const u32x4*)(wrow[t] + w3 + j * 512));
         const uint16_t* al = a_lds[cur] + a_frag;
 #pragma unroll
         for (int i = 0; i < MIW; ++i) af[0][i] = *(const u32x4*)(al + i * 32 * LDS_ROW);
@@ -323,11 +330,14 @@ static void launch_gemm_t(const uint16_t* a, const uint16_t* w, float* C, int M,
     hipLaunchKernelGGL((k_gemm_bf16_deep<8, 1, EPI>), grid, dim3(256), 0, st, a, w, C, M, N, K, per);
     return;
   }
-  switch (mi) {
-    case 1: hipLaunchKernelGGL((k_gemm_bf16<1, EPI>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
-    case 2: hipLaunchKernelGGL((k_gemm_bf16<2, EPI>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
-    case 4: hipLaunchKernelGGL((k_gemm_bf16<4, EPI>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
-    default: hipLaunchKernelGGL((k_gemm_bf16<8, EPI>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
+  switch (mi) {   // a single row block (every decode launch) streams W; several row blocks share it through L2
+    case 1: hipLaunchKernelGGL((k_gemm_bf16<1, EPI, true>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
+    case 2: hipLaunchKernelGGL((k_gemm_bf16<2, EPI, true>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
+    case 4: hipLaunchKernelGGL((k_gemm_bf16<4, EPI, true>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
+    default:
+      if (grid.y == 1) hipLaunchKernelGGL((k_gemm_bf16<8, EPI, true>), grid, dim3(256), 0, st, a, w, C, M, N, K, per);
+      else hipLaunchKernelGGL((k_gemm_bf16<8, EPI, false>), grid, dim3(256), 0, st, a, w, C, M, N, K, per);
+      break;
   }
 }
 
