@@ -145,13 +145,13 @@ def attention_alone(torch, R, iters=20):
     tab = torch.from_numpy(np.maximum(table, 0).astype(np.int32)).to(dev)
     ws_bytes = R.rollout_attn_workspace_bytes(n, int(lens.sum()), Hq, d)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
-    n_work = R.rollout_attn_plan(lens, Hq, d, ws.data_ptr(), ws_bytes)
+    n_work, chunk = R.rollout_attn_plan(lens, Hq, Hkv, d, ws.data_ptr(), ws_bytes)
     out = torch.empty((n, Hq, d), dtype=torch.bfloat16, device=dev)
     stream = torch.cuda.current_stream()
 
     def launch(i):
         R.rollout_attn_decode(pools[i % 3].data_ptr(), Hq, Hkv, d, q.data_ptr(), tab.data_ptr(), table.shape[1], n,
-                              n_work, out.data_ptr(), 0, ws.data_ptr(), stream.cuda_stream)
+                              n_work, chunk, out.data_ptr(), 0, ws.data_ptr(), stream.cuda_stream)
     for i in range(3):
         launch(i)
     torch.cuda.synchronize()

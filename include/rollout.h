@@ -181,17 +181,20 @@ int rollout_attn_write_kv(void* pool_dev, uint32_t n_kv_heads, uint32_t head_dim
 /* Workspace bytes rollout_attn_plan / rollout_attn_decode need for n sequences whose lengths sum to total_ctx. */
 uint64_t rollout_attn_workspace_bytes(uint32_t n, uint64_t total_ctx, uint32_t n_q_heads, uint32_t head_dim);
 
-/* Build the (sequence, 256-token chunk) work list for context lengths ctx_len (host int32 [n], each >= 1) at the
- * head of workspace_dev.  Synchronous (blocking host-to-device copies).  n_work receives the item count. */
-int rollout_attn_plan(const int32_t* ctx_len, uint32_t n, uint32_t n_q_heads, uint32_t head_dim,
-                      void* workspace_dev, uint64_t workspace_bytes, uint32_t* n_work);
+/* Build the (sequence, chunk) work list for context lengths ctx_len (host int32 [n], each >= 1) at the head of
+ * workspace_dev.  The chunk (cached tokens per work item, a multiple of 64 in 256..1024) is chosen from the total
+ * context so that the items make about two rounds over the chip; it is returned in chunk_tokens and must be
+ * passed to rollout_attn_decode.  Synchronous (blocking host-to-device copies). */
+int rollout_attn_plan(const int32_t* ctx_len, uint32_t n, uint32_t n_q_heads, uint32_t n_kv_heads, uint32_t head_dim,
+                      void* workspace_dev, uint64_t workspace_bytes, uint32_t* n_work, uint32_t* chunk_tokens);
 
 /* o[i] = softmax(q[i] K_i^T / sqrt(d)) V_i for the n planned sequences: q_dev bf16 [n, Hq, d]; out_dev fp32
  * [n, Hq, d] if out_fp32 else bf16.  Only enqueues kernels on `stream`; never synchronises or allocates.
- * Errors: EINVAL (null pointer, unsupported head_dim / group size). */
+ * Errors: EINVAL (null pointer, unsupported head_dim / group size, bad chunk_tokens). */
 int rollout_attn_decode(const void* pool_dev, uint32_t n_q_heads, uint32_t n_kv_heads, uint32_t head_dim,
                         const void* q_dev, const int32_t* page_table_dev, uint32_t max_pages, uint32_t n,
-                        uint32_t n_work, void* out_dev, int out_fp32, void* workspace_dev, void* stream);
+                        uint32_t n_work, uint32_t chunk_tokens, void* out_dev, int out_fp32, void* workspace_dev,
+                        void* stream);
 
 /* ---- the bf16 MFMA projection GEMM alone: c[M,N] (fp32) = a[M,K] (bf16, row-major) * w[N,K]^T (bf16) ----
  * The kernels read w in a packed fragment layout (tiles of 32 rows x 64 columns stored in the order the MFMA

@@ -98,8 +98,8 @@ lib.rollout_attn_pool_bytes.restype = _u64
 lib.rollout_attn_write_kv.argtypes = [_vp, _u32, _u32, _vp, _vp, _vp, _vp, _vp, _u32, _u64, _vp]
 lib.rollout_attn_workspace_bytes.argtypes = [_u32, _u64, _u32, _u32]
 lib.rollout_attn_workspace_bytes.restype = _u64
-lib.rollout_attn_plan.argtypes = [_vp, _u32, _u32, _u32, _vp, _u64, C.POINTER(_u32)]
-lib.rollout_attn_decode.argtypes = [_vp, _u32, _u32, _u32, _vp, _vp, _u32, _u32, _u32, _vp, C.c_int, _vp, _vp]
+lib.rollout_attn_plan.argtypes = [_vp, _u32, _u32, _u32, _u32, _vp, _u64, C.POINTER(_u32), C.POINTER(_u32)]
+lib.rollout_attn_decode.argtypes = [_vp, _u32, _u32, _u32, _vp, _vp, _u32, _u32, _u32, _u32, _vp, C.c_int, _vp, _vp]
 lib.rollout_gemm_workspace_bytes.argtypes = [_u32, _u32, _u32]
 lib.rollout_gemm_workspace_bytes.restype = _u64
 lib.rollout_gemm_bf16.argtypes = [_vp, _vp, _vp, _u32, _u32, _u32, _vp, _u64, _vp]
@@ -234,18 +234,19 @@ def rollout_attn_workspace_bytes(n, total_ctx, n_q_heads, head_dim) -> int:
     return lib.rollout_attn_workspace_bytes(n, total_ctx, n_q_heads, head_dim)
 
 
-def rollout_attn_plan(ctx_len, n_q_heads, head_dim, workspace_dev, workspace_bytes) -> int:
+def rollout_attn_plan(ctx_len, n_q_heads, n_kv_heads, head_dim, workspace_dev, workspace_bytes) -> Tuple[int, int]:
+    """Returns (n_work, chunk_tokens)."""
     L = _np(ctx_len, np.int32)
-    nw = _u32()
-    _check(lib.rollout_attn_plan(L.ctypes.data_as(_vp), len(L), n_q_heads, head_dim, workspace_dev, workspace_bytes,
-                                 C.byref(nw)))
-    return nw.value
+    nw, ch = _u32(), _u32()
+    _check(lib.rollout_attn_plan(L.ctypes.data_as(_vp), len(L), n_q_heads, n_kv_heads, head_dim, workspace_dev,
+                                 workspace_bytes, C.byref(nw), C.byref(ch)))
+    return nw.value, ch.value
 
 
 def rollout_attn_decode(pool_dev, n_q_heads, n_kv_heads, head_dim, q_dev, page_table_dev, max_pages, n, n_work,
-                        out_dev, out_fp32, workspace_dev, stream=0) -> None:
+                        chunk_tokens, out_dev, out_fp32, workspace_dev, stream=0) -> None:
     _check(lib.rollout_attn_decode(pool_dev, n_q_heads, n_kv_heads, head_dim, q_dev, page_table_dev, max_pages, n,
-                                   n_work, out_dev, int(out_fp32), workspace_dev, stream))
+                                   n_work, chunk_tokens, out_dev, int(out_fp32), workspace_dev, stream))
 
 
 def rollout_gemm_workspace_bytes(M, N, K) -> int:

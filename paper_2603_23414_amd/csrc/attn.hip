@@ -1,7 +1,7 @@
 // Ragged paged GQA decode attention for gfx950 (the KV-streaming half of the rollout step; the paper,
 // Sec. 2.2, names KV-cache loading as what bounds autoregressive rollout).
 //
-// One wavefront owns one work item = (row, kv head, chunk of ATTN_CHUNK cached tokens).  A row is one
+// One wavefront owns one work item = (row, kv head, chunk of cached tokens; the chunk size is picked per launch).  A row is one
 // query token of one slot; all G query heads that share the kv head are computed from a single pass
 // over the K/V bytes.  The page layout makes both phases stream 16-byte vectors that are contiguous
 // across lanes with no LDS staging of K or V:
@@ -20,7 +20,7 @@ __global__ __launch_bounds__(256) void k_decode_attn(
     const uint8_t* __restrict__ pool, const uint16_t* __restrict__ q, const int* __restrict__ row_slot,
     const int* __restrict__ row_pos, const int* __restrict__ page_table, int max_pages,
     const int2* __restrict__ work, int Hkv, float* __restrict__ part_acc, float* __restrict__ part_ml,
-    void* __restrict__ out, int out_fp32, float scale_log2e) {
+    void* __restrict__ out, int out_fp32, float scale_log2e, int chunk_tokens) {
   constexpr int NCH = D / 8;
   constexpr int DPL = (D + 63) / 64;
   constexpr int KBYTES = PAGE_TOKENS * D * 2;
@@ -35,8 +35,8 @@ __global__ __launch_bounds__(256) void k_decode_attn(
   const int row = it.x, chunk = it.y;
   const int slot = row_slot[row];
   const int ctx = row_pos[row] + 1;
-  const int tok0 = chunk * ATTN_CHUNK;
-  const int tok_end = min(ctx, tok0 + ATTN_CHUNK);
+  const int tok0 = chunk * chunk_tokens;
+  const int tok_end = min(ctx, tok0 + chunk_tokens);
   const int last_page = (ctx - 1) >> 4;
   const int* __restrict__ pt = page_table + (size_t)slot * max_pages;
   const int Hq = Hkv * G;
@@ -51,8 +51,8 @@ __global__ __launch_bounds__(256) void k_decode_attn(
     for (int dd = 0; dd < DPL; ++dd) acc[h][dd] = 0.f;
   }
 
-  // page ids of the whole chunk, fetched once: lane i (mod 16) holds logical page chunk*16 + i
-  const int pgs = pt[min(chunk * (ATTN_CHUNK / PAGE_TOKENS) + (lane & 15), last_page)];
+  // page ids of the whole chunk (at most 64 pages), fetched once: lane i holds logical page chunk*ppc + i
+  const int pgs = pt[min(chunk * (chunk_tokens / PAGE_TOKENS) + lane, last_page)];
 
   for (int t0 = tok0; t0 < tok_end; t0 += 64) {
     const int tile = (t0 - tok0) >> 6;
@@ -142,7 +142,7 @@ __global__ __launch_bounds__(256) void k_decode_attn(
     }
   }
 
-  const int nchunks = (ctx + ATTN_CHUNK - 1) / ATTN_CHUNK;
+  const int nchunks = (ctx + chunk_tokens - 1) / chunk_tokens;
 #pragma unroll
   for (int h = 0; h < G; ++h) {
     const float lsum = wave_sum(l[h]);
@@ -177,10 +177,10 @@ __global__ __launch_bounds__(256) void k_decode_attn(
 template <int D>
 __global__ void k_attn_merge(const int* __restrict__ row_pos, const int* __restrict__ row_wstart, int Hq,
                              const float* __restrict__ part_acc, const float* __restrict__ part_ml,
-                             void* __restrict__ out, int out_fp32) {
+                             void* __restrict__ out, int out_fp32, int chunk_tokens) {
   const int row = blockIdx.x, head = blockIdx.y, dim = threadIdx.x;
   const int ctx = row_pos[row] + 1;
-  const int n = (ctx + ATTN_CHUNK - 1) / ATTN_CHUNK;
+  const int n = (ctx + chunk_tokens - 1) / chunk_tokens;
   if (n == 1) return;
   const int ws = row_wstart[row];
   float mx = NEG_BIG;
@@ -217,14 +217,14 @@ __global__ void k_attn_merge(const int* __restrict__ row_pos, const int* __restr
 // Build the (row, chunk) work list for n_rows rows on the device: one block, any n_rows.
 __global__ __launch_bounds__(1024) void k_attn_worklist(const int* __restrict__ row_pos, int n_rows,
                                                         int2* __restrict__ work, int* __restrict__ row_wstart,
-                                                        int* __restrict__ n_work_out) {
+                                                        int* __restrict__ n_work_out, int chunk_tokens) {
   __shared__ int scan[1024];
   __shared__ int base;
   if (threadIdx.x == 0) base = 0;
   __syncthreads();
   for (int r0 = 0; r0 < n_rows; r0 += 1024) {
     const int r = r0 + threadIdx.x;
-    const int nch = r < n_rows ? (row_pos[r] + 1 + ATTN_CHUNK - 1) / ATTN_CHUNK : 0;
+    const int nch = r < n_rows ? (row_pos[r] + 1 + chunk_tokens - 1) / chunk_tokens : 0;
     scan[threadIdx.x] = nch;
     __syncthreads();
     for (int o = 1; o < 1024; o <<= 1) {
@@ -271,8 +271,9 @@ int attn_supported(int head_dim, int group) {
 }
 
 void launch_attn_worklist(const int* row_pos, int n_rows, int2* work, int* row_wstart, int* n_work_out,
-                          hipStream_t st) {
-  hipLaunchKernelGGL(k_attn_worklist, dim3(1), dim3(1024), 0, st, row_pos, n_rows, work, row_wstart, n_work_out);
+                          int chunk_tokens, hipStream_t st) {
+  hipLaunchKernelGGL(k_attn_worklist, dim3(1), dim3(1024), 0, st, row_pos, n_rows, work, row_wstart, n_work_out,
+                     chunk_tokens);
 }
 
 template <int D, int G>
@@ -282,11 +283,11 @@ static void launch_attn_t(const AttnArgs& a, hipStream_t st, hipEvent_t ev0, hip
   if (ev0) (void)hipEventRecord(ev0, st);
   hipLaunchKernelGGL((k_decode_attn<D, G>), grid, dim3(256), 0, st, (const uint8_t*)a.pool, (const uint16_t*)a.q,
                      a.row_slot, a.row_pos, a.page_table, a.max_pages, a.work, a.Hkv, a.part_acc, a.part_ml, a.out,
-                     a.out_fp32, scale);
+                     a.out_fp32, scale, a.chunk_tokens);
   if (ev1) (void)hipEventRecord(ev1, st);
   if (a.need_merge)
     hipLaunchKernelGGL((k_attn_merge<D>), dim3(a.n_rows, a.Hkv * G), dim3(D), 0, st, a.row_pos, a.row_wstart,
-                       a.Hkv * G, a.part_acc, a.part_ml, a.out, a.out_fp32);
+                       a.Hkv * G, a.part_acc, a.part_ml, a.out, a.out_fp32, a.chunk_tokens);
 }
 
 // ev0 / ev1 (nullable) bracket the main kernel only, not the merge.

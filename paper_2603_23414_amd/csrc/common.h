@@ -4,7 +4,18 @@
 #include <stdint.h>
 
 #define PAGE_TOKENS 16
-#define ATTN_CHUNK 256          // cached tokens per attention work item (16 pages)
+// A decode-attention work item covers `chunk` cached tokens of one (row, kv head); the chunk is chosen per launch:
+// a multiple of 64 between ATTN_CHUNK_MIN and ATTN_CHUNK_MAX, about (sum of contexts) * n_kv_heads / ATTN_TARGET_ITEMS,
+// i.e. roughly two rounds of work items over the chip's resident wavefronts: large chunks when the batch is full
+// (fewer partial results to merge), small chunks when a few long rollouts are left (tail drain) so they still spread.
+#define ATTN_CHUNK_MIN 256
+#define ATTN_CHUNK_MAX 1024         // 64 pages: their ids fit one register across a wavefront
+#define ATTN_TARGET_ITEMS 6144      // 256 CUs x 4 SIMDs x 3 resident waves x 2 rounds
+__host__ __device__ __forceinline__ int attn_pick_chunk(unsigned long long total_ctx, int n_kv_heads) {
+  unsigned long long c = (total_ctx * (unsigned long long)n_kv_heads + ATTN_TARGET_ITEMS - 1) / ATTN_TARGET_ITEMS;
+  c = (c + 63) / 64 * 64;
+  return c < ATTN_CHUNK_MIN ? ATTN_CHUNK_MIN : c > ATTN_CHUNK_MAX ? ATTN_CHUNK_MAX : (int)c;
+}
 #define WAVE 64
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;

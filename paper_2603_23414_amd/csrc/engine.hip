@@ -256,7 +256,8 @@ int load_weights(rollout_ctx* c, const void* weights, size_t weights_bytes) {
 
 // ---- the per-step kernel chain over a set of rows (decode rows or one prefill pass) ---------------------
 void run_layers(rollout_ctx* c, int R, const int* row_slot, const int* row_pos, const int* row_tok, const int2* work,
-                const int* row_wstart, int n_work, bool time_attn, const PfTileHost* pf_tiles = nullptr, int n_tiles = 0) {
+                const int* row_wstart, int n_work, int chunk_tokens, bool time_attn, const PfTileHost* pf_tiles = nullptr,
+                int n_tiles = 0) {
   hipStream_t st = c->stream;
   const int D = c->D, F = c->F, Hq = c->Hq, Hkv = c->Hkv, d = c->d, Nqkv = c->Nqkv;
   const float eps = c->cfg.rms_eps;
@@ -286,6 +287,7 @@ void run_layers(rollout_ctx* c, int R, const int* row_slot, const int* row_pos, 
     a.out = c->attn_out;
     a.out_fp32 = 0;
     a.need_merge = n_work > R;
+    a.chunk_tokens = chunk_tokens;
     if (n_tiles > 0) {
       launch_prefill_attn(pool_l, c->qbuf, pf_tiles, n_tiles, c->sd.page_table, c->max_pages, Hq, Hkv, d, c->attn_out, st);
     } else {
@@ -326,7 +328,7 @@ int run_prefill(rollout_ctx* c, int n_dec, int n_adm) {
     HIPCHK(c, hipMemcpyAsync(c->pf_desc_dev, c->pf_desc_host, sizeof(PrefillDesc) * n_desc, hipMemcpyHostToDevice, st));
     HIPCHK(c, hipMemcpyAsync(c->pf_tiles_dev, c->pf_tiles_host, sizeof(PfTileHost) * n_tiles, hipMemcpyHostToDevice, st));
     launch_prefill_rows(c->sd, c->pf_desc_dev, n_desc, c->pf_row_slot, c->pf_row_pos, c->pf_row_tok, st);
-    run_layers(c, rows, c->pf_row_slot, c->pf_row_pos, c->pf_row_tok, nullptr, nullptr, 0, false, c->pf_tiles_dev, n_tiles);
+    run_layers(c, rows, c->pf_row_slot, c->pf_row_pos, c->pf_row_tok, nullptr, nullptr, 0, 0, false, c->pf_tiles_dev, n_tiles);
     for (int j = 0; j < n_last; ++j) {
       // one tiny gather per finished prompt: h row -> h_final row n_dec + (index among admitted)
       const int src_row = c->pf_last_host[2 * j], dst = n_dec + c->pf_last_host[2 * j + 1];
@@ -346,7 +348,7 @@ int step_impl(rollout_ctx* c, const int32_t* forced_tok, float* logits_out, roll
   hipStream_t st = c->stream;
   int* sh = c->status_host;
   const int Q = c->Q;
-  const int n_dec = sh[STAT_NDEC_NEXT], n_work = sh[STAT_NWORK_NEXT];
+  const int n_dec = sh[STAT_NDEC_NEXT], n_work = sh[STAT_NWORK_NEXT], chunk_tokens = sh[STAT_CHUNK];
   const unsigned long long ctx_sum = (unsigned long long)(unsigned)sh[STAT_CTX_LO] | ((unsigned long long)(unsigned)sh[STAT_CTX_HI] << 32);
   const int n_active = sh[STAT_NACTIVE];
   int n_adm = 0;
@@ -367,7 +369,7 @@ int step_impl(rollout_ctx* c, const int32_t* forced_tok, float* logits_out, roll
   const int n_rows = n_dec + n_adm;
   if (model && n_rows > 0) {
     if (n_dec > 0) {
-      run_layers(c, n_dec, c->sd.row_slot, c->sd.row_pos, c->sd.row_tok, c->sd.work, c->sd.row_wstart, n_work, time_attn);
+      run_layers(c, n_dec, c->sd.row_slot, c->sd.row_pos, c->sd.row_tok, c->sd.work, c->sd.row_wstart, n_work, chunk_tokens, time_attn);
       launch_gather_rows(c->h, c->iota, c->h_final, 0, n_dec, c->D, st);
     }
     if (n_adm > 0) TRY(run_prefill(c, n_dec, n_adm));
@@ -504,7 +506,7 @@ int rollout_init(rollout_ctx** out, const void* weights, size_t weights_bytes, c
   s.qmask = qcap - 1;
   s.tok_stride = f.max_prompt_len + f.max_new_tokens; s.cap = f.max_new_tokens; s.eos_id = f.eos_id;
   s.eos_mode = f.eos_mode; s.mode = f.mode; s.max_staleness = f.max_staleness;
-  s.no_model = (f.debug_flags & ROLLOUT_DEBUG_NO_MODEL) ? 1 : 0; s.V = c->V;
+  s.no_model = (f.debug_flags & ROLLOUT_DEBUG_NO_MODEL) ? 1 : 0; s.V = c->V; s.Hkv = c->Hkv;
   const size_t MS = f.max_seqs, Q = c->Q;
   INIT_TRY(dev_alloc(c, &s.sc, SC_COUNT));
   INIT_TRY(dev_alloc(c, &s.ctr, CT_COUNT));
@@ -529,7 +531,7 @@ int rollout_init(rollout_ctx** out, const void* weights, size_t weights_bytes, c
   INIT_TRY(dev_alloc(c, &s.row_pos, Q));
   INIT_TRY(dev_alloc(c, &s.row_tok, Q));
   INIT_TRY(dev_alloc(c, &s.row_wstart, Q));
-  const size_t dec_work = Q * (size_t)((s.tok_stride + ATTN_CHUNK - 1) / ATTN_CHUNK);
+  const size_t dec_work = Q * (size_t)((s.tok_stride + ATTN_CHUNK_MIN - 1) / ATTN_CHUNK_MIN);
   INIT_TRY(dev_alloc(c, &s.work, dec_work));
   c->status_ints = STAT_HDR + 3 * c->Q;
   INIT_TRY(dev_alloc(c, &s.status, (size_t)c->status_ints));
@@ -850,19 +852,21 @@ static AttnWs attn_ws_layout(uint32_t n, uint64_t max_work, uint32_t Hq, uint32_
   return w;
 }
 uint64_t rollout_attn_workspace_bytes(uint32_t n, uint64_t total_ctx, uint32_t n_q_heads, uint32_t head_dim) {
-  const uint64_t max_work = total_ctx / ATTN_CHUNK + n;
+  const uint64_t max_work = total_ctx / ATTN_CHUNK_MIN + n;
   return attn_ws_layout(n, max_work, n_q_heads, head_dim).total;
 }
 
-int rollout_attn_plan(const int32_t* ctx_len, uint32_t n, uint32_t n_q_heads, uint32_t head_dim, void* workspace_dev,
-                      uint64_t workspace_bytes, uint32_t* n_work) {
-  if (!ctx_len || !workspace_dev || !n_work || n == 0) return fail(nullptr, ROLLOUT_EINVAL, "null argument");
+int rollout_attn_plan(const int32_t* ctx_len, uint32_t n, uint32_t n_q_heads, uint32_t n_kv_heads, uint32_t head_dim,
+                      void* workspace_dev, uint64_t workspace_bytes, uint32_t* n_work, uint32_t* chunk_tokens) {
+  if (!ctx_len || !workspace_dev || !n_work || !chunk_tokens || n == 0 || n_kv_heads == 0)
+    return fail(nullptr, ROLLOUT_EINVAL, "null argument");
   uint64_t total = 0;
   for (uint32_t i = 0; i < n; ++i) {
     if (ctx_len[i] < 1) return fail(nullptr, ROLLOUT_EINVAL, "context lengths must be >= 1");
     total += (uint64_t)ctx_len[i];
   }
-  const uint64_t max_work = total / ATTN_CHUNK + n;
+  const uint64_t max_work = total / ATTN_CHUNK_MIN + n;
+  const int chunk = attn_pick_chunk(total, (int)n_kv_heads);
   const AttnWs w = attn_ws_layout(n, max_work, n_q_heads, head_dim);
   if (w.total > workspace_bytes) return fail(nullptr, ROLLOUT_EINVAL, "workspace too small");
   std::vector<int> rs(n), rp(n), ws(n);
@@ -872,7 +876,7 @@ int rollout_attn_plan(const int32_t* ctx_len, uint32_t n, uint32_t n_q_heads, ui
     rs[i] = (int)i;
     rp[i] = ctx_len[i] - 1;
     ws[i] = (int)work.size();
-    const int nch = (ctx_len[i] + ATTN_CHUNK - 1) / ATTN_CHUNK;
+    const int nch = (ctx_len[i] + chunk - 1) / chunk;
     for (int ch = 0; ch < nch; ++ch) work.push_back(make_int2((int)i, ch));
   }
   uint8_t* base = (uint8_t*)workspace_dev;
@@ -882,14 +886,17 @@ int rollout_attn_plan(const int32_t* ctx_len, uint32_t n, uint32_t n_q_heads, ui
       hipMemcpy(base + w.work, work.data(), 8ull * work.size(), hipMemcpyHostToDevice) != hipSuccess)
     return fail(nullptr, ROLLOUT_EDEVICE, "hipMemcpy failed");
   *n_work = (uint32_t)work.size();
+  *chunk_tokens = (uint32_t)chunk;
   return ROLLOUT_OK;
 }
 
 int rollout_attn_decode(const void* pool_dev, uint32_t n_q_heads, uint32_t n_kv_heads, uint32_t head_dim,
                         const void* q_dev, const int32_t* page_table_dev, uint32_t max_pages, uint32_t n, uint32_t n_work,
-                        void* out_dev, int out_fp32, void* workspace_dev, void* stream) {
+                        uint32_t chunk_tokens, void* out_dev, int out_fp32, void* workspace_dev, void* stream) {
   if (!pool_dev || !q_dev || !page_table_dev || !out_dev || !workspace_dev || n == 0 || n_work < n)
     return fail(nullptr, ROLLOUT_EINVAL, "null argument");
+  if (chunk_tokens < 64 || chunk_tokens > ATTN_CHUNK_MAX || chunk_tokens % 64)
+    return fail(nullptr, ROLLOUT_EINVAL, "chunk_tokens must be a multiple of 64 in 64..1024 (use the planned value)");
   if (n_kv_heads == 0 || n_q_heads % n_kv_heads || !attn_supported((int)head_dim, (int)(n_q_heads / n_kv_heads)))
     return fail(nullptr, ROLLOUT_EINVAL, "unsupported head_dim / query-group size");
   // row arrays and the work list sit where the plan put them (their offsets depend on n only); the partial
@@ -913,6 +920,7 @@ int rollout_attn_decode(const void* pool_dev, uint32_t n_q_heads, uint32_t n_kv_
   a.out = out_dev;
   a.out_fp32 = out_fp32;
   a.need_merge = n_work > n;
+  a.chunk_tokens = (int)chunk_tokens;
   launch_decode_attn(a, (int)head_dim, (int)(n_q_heads / n_kv_heads), (hipStream_t)stream);
   return hipGetLastError() == hipSuccess ? ROLLOUT_OK : fail(nullptr, ROLLOUT_EDEVICE, "kernel launch failed");
 }

@@ -20,9 +20,11 @@ struct AttnArgs {
   void* out;               // [n_rows][Hq*d], bf16 or fp32
   int out_fp32;
   int need_merge;          // some row spans more than one chunk
+  int chunk_tokens;        // cached tokens per work item (multiple of 64, at most 1024)
 };
 int attn_supported(int head_dim, int group);
-void launch_attn_worklist(const int* row_pos, int n_rows, int2* work, int* row_wstart, int* n_work_out, hipStream_t st);
+void launch_attn_worklist(const int* row_pos, int n_rows, int2* work, int* row_wstart, int* n_work_out,
+                          int chunk_tokens, hipStream_t st);
 void launch_decode_attn(const AttnArgs& a, int head_dim, int group, hipStream_t st, hipEvent_t ev0 = nullptr,
                         hipEvent_t ev1 = nullptr);
 void launch_write_kv(void* pool, int Hkv, int head_dim, const void* k, const void* v, const int* tok_seq,
@@ -62,11 +64,11 @@ enum {  // 64-bit counters in SchedDev::ctr
 };
 enum {  // int cells of the status block copied to the host after every scheduler kernel
   STAT_STEP = 0, STAT_R, STAT_NACTIVE, STAT_FIN, STAT_QUEUED, STAT_FREE, STAT_NADM, STAT_NFIN_STEP, STAT_NPRE_STEP,
-  STAT_NDEC_NEXT, STAT_NWORK_NEXT, STAT_CTX_LO, STAT_CTX_HI, STAT_VERSION, STAT_HDR = 16
+  STAT_NDEC_NEXT, STAT_NWORK_NEXT, STAT_CTX_LO, STAT_CTX_HI, STAT_VERSION, STAT_CHUNK, STAT_HDR = 16
 };  // followed by max_slots admission descriptors of 3 ints: slot, sequence-table index, tokens to prefill
 
 struct SchedDev {
-  int Q, max_pages, n_pages, max_seqs, qmask, tok_stride, cap, eos_id, eos_mode, mode, max_staleness, no_model, V;
+  int Q, max_pages, n_pages, max_seqs, qmask, tok_stride, cap, eos_id, eos_mode, mode, max_staleness, no_model, V, Hkv;
   int* sc;
   unsigned long long* ctr;
   int *slot_seq, *slot_npages, *page_table;

@@ -48,11 +48,15 @@ __device__ __forceinline__ void q_push_front(const SchedDev& d, int sidx) {
 __device__ void rebuild_rows_and_status(const SchedDev& d, int* sh, int r_this_step, int n_fin_step, int n_pre_step,
                                         int n_adm) {
   const int t = threadIdx.x;
-  int sidx = -1, pos = 0, nch = 0;
-  if (t < d.Q && (sidx = d.slot_seq[t]) >= 0) {
-    pos = d.seq_prompt_len[sidx] + d.seq_gen_len[sidx] - 1;
-    nch = (pos + 1 + ATTN_CHUNK - 1) / ATTN_CHUNK;
-  }
+  int sidx = -1, pos = 0;
+  if (t < d.Q && (sidx = d.slot_seq[t]) >= 0) pos = d.seq_prompt_len[sidx] + d.seq_gen_len[sidx] - 1;
+  // sum of contexts (chunk choice and byte accounting): reduced through the scan helper on 16-bit halves
+  int lo_tot, hi_tot;
+  block_scan_excl(sidx >= 0 ? ((pos + 1) & 0xFFFF) : 0, &lo_tot, sh);
+  block_scan_excl(sidx >= 0 ? ((pos + 1) >> 16) : 0, &hi_tot, sh);
+  const unsigned long long ctx_total = (unsigned long long)lo_tot + ((unsigned long long)hi_tot << 16);
+  const int chunk = attn_pick_chunk(ctx_total, d.Hkv);
+  const int nch = sidx >= 0 ? (pos + 1 + chunk - 1) / chunk : 0;
   int n_active, n_work;
   const int rank = block_scan_excl(sidx >= 0 ? 1 : 0, &n_active, sh);
   const int wstart = block_scan_excl(nch, &n_work, sh);
@@ -63,15 +67,11 @@ __device__ void rebuild_rows_and_status(const SchedDev& d, int* sh, int r_this_s
     d.row_wstart[rank] = wstart;
     for (int c = 0; c < nch; ++c) d.work[wstart + c] = make_int2(rank, c);
   }
-  // sum of contexts (for byte accounting): two-level reduction through the scan helper on 16-bit halves
-  int lo_tot, hi_tot;
-  block_scan_excl(sidx >= 0 ? ((pos + 1) & 0xFFFF) : 0, &lo_tot, sh);
-  block_scan_excl(sidx >= 0 ? ((pos + 1) >> 16) : 0, &hi_tot, sh);
   if (t == 0) {
     d.sc[SC_NDEC] = n_active;
     d.sc[SC_NPRE] = 0;
     d.sc[SC_NWORK] = n_work;
-    const unsigned long long ctx = (unsigned long long)lo_tot + ((unsigned long long)hi_tot << 16);
+    const unsigned long long ctx = ctx_total;
     int* s = d.status;
     s[STAT_STEP] = d.sc[SC_STEP];
     s[STAT_R] = r_this_step;
@@ -87,6 +87,7 @@ __device__ void rebuild_rows_and_status(const SchedDev& d, int* sh, int r_this_s
     s[STAT_CTX_LO] = (int)(ctx & 0xFFFFFFFFull);
     s[STAT_CTX_HI] = (int)(ctx >> 32);
     s[STAT_VERSION] = d.sc[SC_VERSION];
+    s[STAT_CHUNK] = chunk;
   }
 }
 

@@ -28,12 +28,12 @@ def _run_case(lens, Hq, Hkv, d, seed, out_fp32=True, poison=True):
                             tab_d.data_ptr(), table.shape[1], int(lens.sum()))
     ws_bytes = R.rollout_attn_workspace_bytes(n, int(lens.sum()), Hq, d)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
-    n_work = R.rollout_attn_plan(lens, Hq, d, ws.data_ptr(), ws_bytes)
-    assert n_work == int(((lens + 255) // 256).sum())
+    n_work, chunk = R.rollout_attn_plan(lens, Hq, Hkv, d, ws.data_ptr(), ws_bytes)
+    assert chunk % 64 == 0 and 256 <= chunk <= 1024 and n_work == int(((lens + chunk - 1) // chunk).sum())
     q_d = t(q.view(np.int16))
     out = torch.full((n, Hq, d), float("nan"), dtype=torch.float32 if out_fp32 else torch.bfloat16, device=dev)
     R.rollout_attn_decode(pool.data_ptr(), Hq, Hkv, d, q_d.data_ptr(), tab_d.data_ptr(), table.shape[1], n, n_work,
-                          out.data_ptr(), out_fp32, ws.data_ptr())
+                          chunk, out.data_ptr(), out_fp32, ws.data_ptr())
     torch.cuda.synchronize()
     got = out.float().cpu().numpy().astype(np.float64)
     # oracle on the same bf16-exact operands, contiguous pools built by the oracle's own addressing

@@ -28,10 +28,10 @@ def test_attention_case_full_size_sampled_rows():
     tab = torch.from_numpy(np.maximum(table, 0).astype(np.int32)).to(dev)
     ws_bytes = R.rollout_attn_workspace_bytes(n, int(lens.sum()), Hq, d)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
-    n_work = R.rollout_attn_plan(lens, Hq, d, ws.data_ptr(), ws_bytes)
+    n_work, chunk = R.rollout_attn_plan(lens, Hq, Hkv, d, ws.data_ptr(), ws_bytes)
     out = torch.empty((n, Hq, d), dtype=torch.float32, device=dev)
     R.rollout_attn_decode(pool.data_ptr(), Hq, Hkv, d, q.data_ptr(), tab.data_ptr(), table.shape[1], n, n_work,
-                          out.data_ptr(), 1, ws.data_ptr())
+                          chunk, out.data_ptr(), 1, ws.data_ptr())
     torch.cuda.synchronize()
     got = out.cpu().numpy().astype(np.float64)
     assert np.isfinite(got).all()
