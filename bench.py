@@ -185,6 +185,67 @@ def attention_alone(torch, R, iters=20):
                 pure_read_ceiling_gbps=float(np.median(rd[2:])))
 
 
+def full_run(torch, R, W, wl, m, L):
+    """Whole job, cold start to drain: every prompt prefilled, every token decoded, harvest whenever a group is ready
+    (with the boundary work that entails), tail drain included.  Reports whole-job tokens/s and the three bubble ratios."""
+    blob = device_weights(torch, m, wl.seed_weights)
+    page_bytes = wl.model.n_layers * wl.model.n_kv_heads * 2 * 16 * wl.model.head_dim * 2
+    pool_bytes = wl.kv_pool_bytes or min(120 * 10**9, wl.max_slots * ((wl.prompt_len + wl.cap + 15) // 16) * page_bytes)
+    cfg = R.make_cfg(m, max_slots=wl.max_slots, max_prompt_len=wl.prompt_len, max_new_tokens=wl.cap, max_seqs=wl.n_prompts,
+                     kv_pool_bytes=pool_bytes * m.n_layers // wl.model.n_layers, weights_on_device=1,
+                     max_staleness=wl.max_staleness, debug_flags=R.ROLLOUT_DEBUG_TIME_ATTN)
+    ctx = R.rollout_init((blob.data_ptr(), blob.numel() * 2), cfg)
+    del blob
+    torch.cuda.empty_cache()
+    prompts = W.make_prompts(wl.n_prompts, wl.prompt_len, m.vocab, wl.seed_prompts)
+    offs = np.arange(wl.n_prompts + 1, dtype=np.uint32) * wl.prompt_len
+    R.rollout_submit(ctx, prompts.reshape(-1), offs, L.astype(np.uint32))
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    idle_time = 0.0
+    harvested = steps = 0
+    last_print = t_start
+    while True:
+        t0 = time.perf_counter()
+        i = R.rollout_step(ctx)
+        dt = time.perf_counter() - t0
+        idle_time += (wl.max_slots - i.n_ran) * dt
+        steps += 1
+        if i.n_finished_unharvested >= wl.harvest:
+            ng, recs, tk, lp = R.rollout_harvest(ctx, wl.harvest, 0, want_logp=True)
+            harvested += len(recs)
+        if i.n_active == 0 and i.n_queued == 0:
+            break
+        if time.perf_counter() - last_print > 30:
+            last_print = time.perf_counter()
+            print(f"[full-run] step {steps} active {i.n_active} queued {i.n_queued} harvested {harvested} "
+                  f"elapsed {last_print - t_start:.0f}s", file=sys.stderr, flush=True)
+    ng, recs, tk, lp = R.rollout_harvest(ctx, wl.harvest, R.ROLLOUT_FLUSH, want_logp=True)
+    harvested += len(recs)
+    torch.cuda.synchronize()
+    T = time.perf_counter() - t_start
+    st = R.rollout_stats(ctx)
+    R.rollout_destroy(ctx)
+    assert harvested == wl.n_prompts and st.gen_tokens == int(L.sum())
+    kvb = m.n_kv_heads * 2 * m.head_dim * 2
+    out = dict(metric=f"rollout tokens/s, whole job ({wl.name})", value=st.gen_tokens / T, unit="tokens/s", n_gpus=1,
+               steps=int(st.steps), warmup=0, ms_per_step=1e3 * T / st.steps, higher_is_better=True, scaling="weak",
+               vs_baseline=None, dtype="bf16", data="synthetic",
+               config=dict(workload=f"{wl.name}: whole job from a cold start to drain, {m.n_layers} layers, Q={wl.max_slots}, "
+                                    f"{wl.n_prompts} prompts x {wl.prompt_len}, cap {wl.cap}, harvest {wl.harvest}, "
+                                    f"max_staleness {wl.max_staleness}",
+                           wall_s=T, gen_tokens=int(st.gen_tokens), prefill_tokens=int(st.prefill_tokens),
+                           n_stale=int(st.n_stale), n_preempt=int(st.n_preempt)),
+               bubble_ratio=dict(steps=st.idle / (wl.max_slots * st.steps),
+                                 steps_while_queue_non_empty=(st.idle_q / (wl.max_slots * st.steps_q)) if st.steps_q else 0.0,
+                                 wall_time_weighted=idle_time / (wl.max_slots * T)),
+               roofline=dict(bound="hbm", kernel="k_decode_attn, all decode launches of the job",
+                             achieved=(st.attn_kv_tokens * kvb) / max(st.attn_ms, 1e-9) / 1e6, peak=8000.0, unit="GB/s",
+                             frac=(st.attn_kv_tokens * kvb) / max(st.attn_ms, 1e-9) / 1e6 / 8000.0, traffic=None,
+                             launches=int(st.attn_launches)))
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -194,6 +255,9 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="debug: override the layer count (invalidates the result)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-attn-alone", action="store_true")
+    ap.add_argument("--full-run", action="store_true",
+                    help="run the whole workload from a cold start to drain and report whole-job tokens/s "
+                         "(minutes of GPU time; not the default bench line)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -204,6 +268,8 @@ def main():
     wl = W.CONFIGS[args.workload]
     m = wl.model if not args.layers else wl.model.with_layers(args.layers)
     L = W.make_target_lengths(wl.n_prompts, wl.len_mu, wl.len_sigma, wl.cap, wl.seed_lengths)
+    if args.full_run:
+        return full_run(torch, R, W, wl, m, L)
     t0 = time.time()
     snap, full = scheduler_snapshot(wl, L)
     print(f"[bench] scheduler oracle: {full} snapshot step {snap['step']} ({time.time() - t0:.1f}s)", file=sys.stderr)

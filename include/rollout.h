@@ -118,6 +118,16 @@ typedef struct rollout_stats_t {
  * max_slots <= 1024, d_model, d_ffn multiples of 64), ENOMEM, EDEVICE. */
 int rollout_init(rollout_ctx** out, const void* weights, size_t weights_bytes, const rollout_cfg* cfg);
 
+/* Sec. 3.2 / Sec. 3.3: install the policy produced by the trainer's update (same shape, same blob format and location
+ * as at rollout_init).  Call it between steps, normally right after a rollout_harvest that returned groups.  Running
+ * rollouts keep their tokens, log-probs and KV pages: tokens generated afterwards use the new weights on top of the
+ * cache they already have, and their log-probs are recorded under the policy that produced them, so a harvested
+ * trajectory carries the concatenation of old- and new-policy segments (the pi_old of eq. 1).  With
+ * max_staleness >= 0 the boundary of that harvest has already released the caches that are too old; they are rebuilt
+ * under the new weights by re-prefill.  Errors: EINVAL (blob size does not match the shape; the ctx is unusable
+ * afterwards), ENOMEM, EDEVICE. */
+int rollout_update_weights(rollout_ctx*, const void* weights, size_t weights_bytes);
+
 /* Fig. 2 step 1 "feed prompts": append n prompts to the FIFO queue.  tokens = concatenated ids,
  * offsets[n+1] delimits them, target_len[i] > 0 forces EOS as the target_len-th generated token
  * (Sec. 4.4.1 pins per-sample lengths this way), 0 = no forced length.  first_seq_id (nullable) receives the id

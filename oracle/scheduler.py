@@ -285,6 +285,10 @@ class OracleRollout:
         for s in sorted(out, key=lambda x: -x.seq_id):    # queue front ends up in ascending seq_id
             self.queue.appendleft(s)
 
+    # ---- policy update (Sec. 3.2): later tokens come from the new weights; caches and recorded log-probs stay ------
+    def update_weights(self, model) -> None:
+        self.model = model
+
     # ---- reporting ---------------------------------------------------------------------------
     def bubble_ratio(self) -> float:
         return self.idle / (self.Q * self.step_no) if self.step_no else 0.0

@@ -16,7 +16,8 @@ __all__ = [
     "rollout_peek", "rollout_slot_pages", "rollout_destroy", "rollout_last_error",
     "rollout_attn_pool_bytes", "rollout_attn_write_kv", "rollout_attn_workspace_bytes", "rollout_attn_plan",
     "rollout_attn_decode", "rollout_gemm_workspace_bytes", "rollout_gemm_bf16", "rollout_stream_copy",
-    "rollout_stream_read", "rollout_gemm_packed_bytes", "rollout_gemm_pack_weights", "make_cfg",
+    "rollout_stream_read", "rollout_gemm_packed_bytes", "rollout_gemm_pack_weights", "rollout_update_weights",
+    "make_cfg",
     "ROLLOUT_FLUSH", "ROLLOUT_DEBUG_NO_MODEL", "ROLLOUT_DEBUG_TIME_ATTN", "ROLLOUT_MODE_PARTIAL",
     "ROLLOUT_MODE_ONPOLICY", "ROLLOUT_MODE_SYNC", "ROLLOUT_EOS_FORCED_ONLY", "ROLLOUT_EOS_NATURAL_OR_FORCED",
     "EXPORTS",
@@ -39,7 +40,7 @@ EXPORTS = [
     "rollout_peek", "rollout_slot_pages", "rollout_last_error", "rollout_destroy", "rollout_attn_pool_bytes",
     "rollout_attn_write_kv", "rollout_attn_workspace_bytes", "rollout_attn_plan", "rollout_attn_decode",
     "rollout_gemm_workspace_bytes", "rollout_gemm_bf16", "rollout_stream_copy", "rollout_stream_read",
-    "rollout_gemm_packed_bytes", "rollout_gemm_pack_weights",
+    "rollout_gemm_packed_bytes", "rollout_gemm_pack_weights", "rollout_update_weights",
 ]
 
 
@@ -81,6 +82,7 @@ class rollout_stats_t(C.Structure):
 
 _vp, _u32, _u64, _i32 = C.c_void_p, C.c_uint32, C.c_uint64, C.c_int32
 lib.rollout_init.argtypes = [C.POINTER(_vp), _vp, C.c_size_t, C.POINTER(rollout_cfg)]
+lib.rollout_update_weights.argtypes = [_vp, _vp, C.c_size_t]
 lib.rollout_submit.argtypes = [_vp, _vp, _vp, _vp, _u32, C.POINTER(_u64)]
 lib.rollout_step.argtypes = [_vp, C.POINTER(rollout_step_info)]
 lib.rollout_step_forced.argtypes = [_vp, _vp, _vp, C.POINTER(rollout_step_info)]
@@ -153,6 +155,15 @@ def rollout_init(weights, cfg: rollout_cfg):
         rc = lib.rollout_init(C.byref(ctx), w.ctypes.data_as(_vp), w.nbytes, C.byref(cfg))
     _check(rc)
     return ctx
+
+
+def rollout_update_weights(ctx, weights) -> None:
+    if isinstance(weights, tuple):
+        ptr, nbytes = weights
+        _check(lib.rollout_update_weights(ctx, _vp(ptr), nbytes), ctx)
+    else:
+        w = np.ascontiguousarray(weights)
+        _check(lib.rollout_update_weights(ctx, w.ctypes.data_as(_vp), w.nbytes), ctx)
 
 
 def rollout_submit(ctx, tokens, offsets, target_len) -> int:

@@ -197,25 +197,13 @@ struct BlobReader {
   }
 };
 
-int load_weights(rollout_ctx* c, const void* weights, size_t weights_bytes) {
-  const size_t D = c->D, F = c->F, V = c->V, qd = (size_t)c->Hq * c->d, kvd = (size_t)c->Hkv * c->d;
-  const auto pad32 = [](size_t n) { return (n + 31) / 32 * 32; };
-  BlobReader br{c, (const uint8_t*)weights, c->cfg.weight_dtype == 0 ? (size_t)4 : (size_t)2, 0, weights_bytes};
-  // staging must hold the largest assembled matrix (with its padded rows)
-  const size_t big = std::max({pad32(V) * D, 2 * F * D, pad32((size_t)c->Nqkv) * D, pad32(D) * qd, pad32(D) * F});
-  if (!c->cfg.weights_on_device) {
-    br.tmp_bytes = big * br.esz;
-    if (hipMalloc(&br.tmp, br.tmp_bytes) != hipSuccess) return fail(c, ROLLOUT_ENOMEM, "hipMalloc failed (weight staging)");
-  }
-  if (hipMalloc((void**)&br.rowmajor, big * 2) != hipSuccess) return fail(c, ROLLOUT_ENOMEM, "hipMalloc failed (weight staging)");
-  struct Guard {   // staging is only needed while loading
-    BlobReader& b;
-    ~Guard() { if (b.tmp) (void)hipFree(b.tmp); if (b.rowmajor) (void)hipFree(b.rowmajor); }
-  } guard{br};
+inline size_t pad32(size_t n) { return (n + 31) / 32 * 32; }
+
+int alloc_weights(rollout_ctx* c) {
+  const size_t D = c->D, F = c->F, V = c->V, qd = (size_t)c->Hq * c->d;
   TRY(dev_alloc(c, &c->embed, V * D));
   TRY(dev_alloc(c, &c->lm_head, pad32(V) * D));
   TRY(dev_alloc(c, &c->final_norm, D));
-  TRY(br.take(V, D, c->embed, 0, 0, 0, 0));
   c->layers.resize(c->NL);
   for (int l = 0; l < c->NL; ++l) {
     LayerW& L = c->layers[l];
@@ -225,13 +213,38 @@ int load_weights(rollout_ctx* c, const void* weights, size_t weights_bytes) {
     TRY(dev_alloc(c, &L.ffn_norm, D));
     TRY(dev_alloc(c, &L.wgu, 2 * F * D));
     TRY(dev_alloc(c, &L.wdown, pad32(D) * F));
+    if (c->cfg.qkv_bias) TRY(dev_alloc(c, &L.bqkv, (size_t)c->Nqkv));
+  }
+  return 0;
+}
+
+// Convert and repack a weights blob into the engine's buffers (used by rollout_init and rollout_update_weights).
+int fill_weights(rollout_ctx* c, const void* weights, size_t weights_bytes) {
+  const size_t D = c->D, F = c->F, V = c->V, qd = (size_t)c->Hq * c->d, kvd = (size_t)c->Hkv * c->d;
+  BlobReader br{c, (const uint8_t*)weights, c->cfg.weight_dtype == 0 ? (size_t)4 : (size_t)2, 0, weights_bytes};
+  // staging must hold the largest assembled matrix (with its padded rows)
+  const size_t big = std::max({pad32(V) * D, 2 * F * D, pad32((size_t)c->Nqkv) * D, pad32(D) * qd, pad32(D) * F});
+  if (!c->cfg.weights_on_device) {
+    br.tmp_bytes = big * br.esz;
+    if (hipMalloc(&br.tmp, br.tmp_bytes) != hipSuccess) return fail(c, ROLLOUT_ENOMEM, "hipMalloc failed (weight staging)");
+  }
+  if (hipMalloc((void**)&br.rowmajor, big * 2) != hipSuccess) {
+    if (br.tmp) (void)hipFree(br.tmp);
+    return fail(c, ROLLOUT_ENOMEM, "hipMalloc failed (weight staging)");
+  }
+  struct Guard {   // staging is only needed while loading
+    BlobReader& b;
+    ~Guard() { if (b.tmp) (void)hipFree(b.tmp); if (b.rowmajor) (void)hipFree(b.rowmajor); }
+  } guard{br};
+  TRY(br.take(V, D, c->embed, 0, 0, 0, 0));
+  for (int l = 0; l < c->NL; ++l) {
+    LayerW& L = c->layers[l];
     TRY(br.take(1, D, L.attn_norm, 1, 0, 0, 0));
     TRY(br.take(qd, D, br.rowmajor, 0, 0, 0, 0));
     TRY(br.take(kvd, D, br.rowmajor, 0, qd, 0, 0));
     TRY(br.take(kvd, D, br.rowmajor, 0, qd + kvd, 0, 0));
     TRY(br.pack((size_t)c->Nqkv, D, L.wqkv));
     if (c->cfg.qkv_bias) {
-      TRY(dev_alloc(c, &L.bqkv, (size_t)c->Nqkv));
       // biases are [1, n] rows in the blob: load them as n rows of one column so they land contiguously
       TRY(br.take(qd, 1, L.bqkv, 1, 0, 0, 0));
       TRY(br.take(kvd, 1, L.bqkv, 1, qd, 0, 0));
@@ -594,7 +607,8 @@ int rollout_init(rollout_ctx** out, const void* weights, size_t weights_bytes, c
     s.row_argmax = c->row_argmax;
     s.row_lse = c->row_lse;
     s.logits = c->logits;
-    INIT_TRY(load_weights(c, weights, weights_bytes));
+    INIT_TRY(alloc_weights(c));
+    INIT_TRY(fill_weights(c, weights, weights_bytes));
     if (f.debug_flags & ROLLOUT_DEBUG_TIME_ATTN) {
       c->ev.resize(2 * (size_t)c->NL);
       for (auto& e : c->ev) INIT_HIP(hipEventCreate(&e));
@@ -645,6 +659,17 @@ int rollout_submit(rollout_ctx* c, const int32_t* tokens, const uint32_t* offset
   launch_sched_submit(c->sd, c->sub_dev, c->tok_stage_dev, (int)n, c->stream);
   TRY(sync_status(c));
   return ROLLOUT_OK;
+}
+
+int rollout_update_weights(rollout_ctx* c, const void* weights, size_t weights_bytes) {
+  if (!c || !weights) return fail(c, ROLLOUT_EINVAL, "null argument");
+  if (c->dead) return fail(c, ROLLOUT_EDEVICE, "context unusable after an earlier device error");
+  if (c->cfg.debug_flags & ROLLOUT_DEBUG_NO_MODEL) return ROLLOUT_OK;
+  HIPCHK(c, hipSetDevice(c->cfg.device));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  const int r = fill_weights(c, weights, weights_bytes);
+  if (r == ROLLOUT_EINVAL) c->dead = true;   // buffers may hold a mix of old and new tensors
+  return r;
 }
 
 int rollout_step(rollout_ctx* c, rollout_step_info* info) { return step_impl(c, nullptr, nullptr, info); }

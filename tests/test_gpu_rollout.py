@@ -94,7 +94,7 @@ def test_scheduler_hand_built_preemption_case():
 
 
 def _teacher_forced(m, blob, prompts, L, *, Q, cap, G, max_prompt_len=None, kv_pool_pages=0, max_staleness=-1,
-                    tol=2e-2, seed_pages=0):
+                    tol=2e-2, seed_pages=0, swap_blob=None):
     """Run oracle (with the model) and engine in lockstep; the engine is fed the oracle's token at every step and
     its fp32 logits rows are compared.  Returns (worst |logit error|, rows compared, argmax agreement)."""
     import paper_2603_23414_amd as R
@@ -133,6 +133,12 @@ def _teacher_forced(m, blob, prompts, L, *, Q, cap, G, max_prompt_len=None, kv_p
             if len(orc.finished) >= G:
                 recs, tk, lp, flat = _harvest_both(R, ctx, orc, G)
                 harvested += [(r, tk, lp, s) for r, s in zip(recs, flat)]
+                if swap_blob is not None:                        # the trainer's update arrives at this boundary
+                    from oracle import OracleModel
+                    w2 = {k: W.bf16_bits_to_f32(v) for k, v in W.split_weights(swap_blob, m).items()}
+                    orc.update_weights(OracleModel(m, w2, np.float64))
+                    R.rollout_update_weights(ctx, swap_blob)
+                    swap_blob = None
         recs, tk, lp, flat = _harvest_both(R, ctx, orc, G, flush=True)
         harvested += [(r, tk, lp, s) for r, s in zip(recs, flat)]
         assert len(harvested) == len(prompts)
@@ -178,6 +184,19 @@ def test_gqa_shapes_ragged_prompts_staleness_and_preemption(shape):
                                          max_prompt_len=150, kv_pool_pages=40, max_staleness=1, seed_pages=7)
     assert rows >= int(L.sum())
     assert agree >= 0.95 * rows
+
+
+@pytest.mark.parametrize("stale", [-1, 0])
+def test_weight_update_at_a_boundary(stale):
+    """A new policy is installed after the first harvest: later logits must follow the new weights on top of the caches
+    that survive (stale = -1: old-policy KV is kept; stale = 0: it is rebuilt by re-prefill under the new weights)."""
+    c = W.CONFIGS["tiny"]
+    m = c.model
+    prompts = list(W.make_prompts(c.n_prompts, c.prompt_len, m.vocab, c.seed_prompts))
+    L = W.make_target_lengths(c.n_prompts, c.len_mu, c.len_sigma, c.cap, c.seed_lengths)
+    worst, rows, agree = _teacher_forced(m, W.make_weights(m, 1), prompts, L, Q=5, cap=c.cap, G=2, max_staleness=stale,
+                                         swap_blob=W.make_weights(m, 77))
+    assert rows >= int(L.sum())
 
 
 def test_prompt_longer_than_one_prefill_pass():

@@ -236,3 +236,61 @@ def test_full_size_configs_run_and_report_bubbles():
                                                for b in range(0, c.n_prompts, c.max_slots)))
     assert abs(res[MODE_SYNC] - closed) < 1e-12
     assert res[MODE_PARTIAL] < res[MODE_SYNC]
+
+
+def _tiny_model(seed):
+    m = W.ModelShape(1, 16, 2, 2, 8, 32, 12, 1e-5, 1e4, 0)
+    g = np.random.default_rng(seed)
+    w = {n: g.standard_normal((r, c)) * 0.5 for n, r, c in W.weight_layout(m)}
+    return m, OracleModel(m, w)
+
+
+def _run_with_swap(stale, swap_model, prompts, L):
+    m, old = _tiny_model(3)
+    pool = PagedKV(1, 40, 4, 2, 8, np.float64)
+    o = OracleRollout(max_slots=3, page_tokens=4, n_pages=40, max_new_tokens=12, eos_id=11, model=old, kv_pool=pool,
+                      max_staleness=stale)
+    o.submit(prompts, L)
+    swapped_at = None
+    while o.queue or any(x is not None for x in o.slots):
+        o.step()
+        if len(o.finished) >= 2:
+            o.harvest(2)
+            if swapped_at is None and swap_model is not None:
+                o.update_weights(swap_model)
+                swapped_at = o.step_no
+    o.harvest(2, flush=True)
+    return o, swapped_at
+
+
+def test_update_weights_same_policy_changes_nothing_and_new_policy_takes_over():
+    """Sec. 3.2: tokens after an update come from the new policy; earlier tokens and their log-probs stay as generated.
+    With max_staleness = 0 every surviving cache is rebuilt under the new weights, so each later token must equal the
+    greedy token of a fresh full-prefix recompute under the NEW model; earlier ones under the OLD model."""
+    g = np.random.default_rng(9)
+    prompts = [g.integers(0, 11, 3).astype(np.int32) for _ in range(6)]
+    L = [2, 9, 3, 10, 8, 4]
+    m, old = _tiny_model(3)
+    _, new = _tiny_model(4)
+    base, _ = _run_with_swap(0, None, prompts, L)
+    same, _ = _run_with_swap(0, old, prompts, L)
+    assert [s.tokens for s in same.seqs] == [s.tokens for s in base.seqs]
+    assert [s.logp for s in same.seqs] == [s.logp for s in base.seqs]
+    swp, at = _run_with_swap(0, new, prompts, L)
+    assert at is not None
+    changed = 0
+    for s, b in zip(swp.seqs, base.seqs):
+        # tokens emitted at steps before the swap are untouched; reconstruct each token's emission step from the end
+        first_step = s.completion_step - s.gen_len + 1 if s.n_preempt == 0 else None
+        for t in range(s.gen_len):
+            forced = t + 1 == s.target_len
+            if first_step is None:
+                continue
+            step_t = first_step + t
+            model = old if step_t < at else new
+            lg = model.full_recompute(s.prompt + s.tokens[:t])
+            assert s.tokens[t] == (11 if forced else int(np.argmax(lg))), (s.seq_id, t)
+            if step_t < at:
+                assert s.logp[t] == b.logp[t]
+        changed += int(s.tokens != b.tokens)
+    assert changed > 0
