@@ -70,6 +70,10 @@ typedef struct rollout_cfg {
   uint64_t page_seed;         /* seeds the initial order of the page free list */
   int32_t device;             /* HIP device ordinal */
   uint32_t reserved;
+  /* sampling (Sec. 4.1 collects several sampled responses per prompt: submit the prompt once per response) */
+  float temperature;          /* 0 = greedy argmax; > 0 = draw from softmax(logits / temperature) by Gumbel-max */
+  uint32_t reserved2;
+  uint64_t sample_seed;       /* key of the counter-based generator; the counter is (vocab index, token index, seq_id) */
 } rollout_cfg;
 
 typedef struct rollout_step_info {
@@ -138,7 +142,8 @@ int rollout_submit(rollout_ctx*, const int32_t* tokens, const uint32_t* offsets,
                    uint32_t n, uint64_t* first_seq_id);
 
 /* One global decode step (Sec. 3.1): refill free slots from the queue head (prefill), decode one token for
- * every other running request, emit (forced EOS / greedy argmax, lowest index on ties), evict finished
+ * every other running request, emit (forced EOS / greedy argmax, lowest index on ties / a Gumbel-max draw when
+ * cfg.temperature > 0: argmax_j logits_j / T - log(-log u_j), u_j from Philox4x32-10), evict finished
  * rollouts and free their pages, grow pages (preempting the shortest rollout if the pool is empty).
  * info is nullable. */
 int rollout_step(rollout_ctx*, rollout_step_info* info);

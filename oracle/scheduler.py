@@ -42,6 +42,7 @@ from typing import List, Optional, Sequence
 import numpy as np
 
 from .model import greedy_token, log_prob
+from .sampling import log_prob_at, sample_token
 
 QUEUED, ACTIVE, FINISHED, HARVESTED = 0, 1, 2, 3
 MODE_PARTIAL, MODE_ONPOLICY, MODE_SYNC = 0, 1, 2
@@ -92,13 +93,15 @@ class Seq:
 class OracleRollout:
     def __init__(self, *, max_slots: int, page_tokens: int, n_pages: int, max_new_tokens: int,
                  eos_id: int, eos_mode: int = EOS_FORCED_ONLY, mode: int = MODE_PARTIAL,
-                 max_staleness: int = -1, page_seed: int = 0, model=None, kv_pool=None):
+                 max_staleness: int = -1, page_seed: int = 0, model=None, kv_pool=None,
+                 temperature: float = 0.0, sample_seed: int = 0):
         self.Q = max_slots
         self.pt = page_tokens
         self.cap = max_new_tokens
         self.eos_id, self.eos_mode, self.mode = eos_id, eos_mode, mode
         self.max_staleness = max_staleness
         self.model, self.kv_pool = model, kv_pool
+        self.temperature, self.sample_seed = temperature, sample_seed   # 0 = greedy
         self.n_pages = n_pages
         self.free = splitmix64_permutation(n_pages, page_seed)  # stack: pop from the end
         self.slots: List[Optional[Seq]] = [None] * max_slots
@@ -193,12 +196,18 @@ class OracleRollout:
         for s in ran:                                     # ascending slot id
             lg = logits_of.get(s.slot)
             forced = s.target_len > 0 and s.gen_len + 1 == s.target_len
+            sampling = self.temperature > 0.0 and lg is not None
             if forced:
                 tok = self.eos_id
+            elif sampling:
+                tok = sample_token(lg, self.temperature, self.sample_seed, s.seq_id, s.gen_len)
             else:
                 tok = greedy_token(lg) if lg is not None else 0
             s.tokens.append(tok)
-            s.logp.append(log_prob(lg, tok) if lg is not None else 0.0)
+            if lg is None:
+                s.logp.append(0.0)
+            else:
+                s.logp.append(log_prob_at(lg, tok, self.temperature) if sampling else log_prob(lg, tok))
             fin = forced or (self.eos_mode == EOS_NATURAL_OR_FORCED and tok == self.eos_id) \
                 or s.gen_len >= self.cap
             if fin:

@@ -58,7 +58,8 @@ class rollout_cfg(C.Structure):
         ("kv_pool_bytes", C.c_uint64), ("max_prompt_len", C.c_uint32), ("max_new_tokens", C.c_uint32),
         ("max_seqs", C.c_uint32), ("eos_id", C.c_int32), ("eos_mode", C.c_uint32), ("mode", C.c_uint32),
         ("max_staleness", C.c_int32), ("grouped_loading", C.c_uint32), ("debug_flags", C.c_uint32),
-        ("page_seed", C.c_uint64), ("device", C.c_int32), ("reserved", C.c_uint32)]
+        ("page_seed", C.c_uint64), ("device", C.c_int32), ("reserved", C.c_uint32), ("temperature", C.c_float),
+        ("reserved2", C.c_uint32), ("sample_seed", C.c_uint64)]
 
 
 class rollout_step_info(C.Structure):
@@ -130,7 +131,7 @@ def _np(a, dtype):
 
 def make_cfg(shape, *, max_slots, max_prompt_len, max_new_tokens, max_seqs, kv_pool_bytes=0, weight_dtype=1,
              weights_on_device=0, eos_mode=0, mode=0, max_staleness=-1, grouped_loading=0, debug_flags=0,
-             page_seed=0, device=0) -> rollout_cfg:
+             page_seed=0, device=0, temperature=0.0, sample_seed=0) -> rollout_cfg:
     """Fill a rollout_cfg from a model shape object (fields as in workloads.ModelShape)."""
     c = rollout_cfg()
     for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab", "qkv_bias"):
@@ -141,6 +142,7 @@ def make_cfg(shape, *, max_slots, max_prompt_len, max_new_tokens, max_seqs, kv_p
     c.max_prompt_len, c.max_new_tokens, c.max_seqs = max_prompt_len, max_new_tokens, max_seqs
     c.eos_id, c.eos_mode, c.mode, c.max_staleness = int(shape.vocab) - 1, eos_mode, mode, max_staleness
     c.grouped_loading, c.debug_flags, c.page_seed, c.device = grouped_loading, debug_flags, page_seed, device
+    c.temperature, c.sample_seed = float(temperature), int(sample_seed)
     return c
 
 

@@ -119,17 +119,59 @@ __global__ __launch_bounds__(1024) void k_rope_kvwrite(const float* __restrict__
   }
 }
 
-// Per row of fp32 logits: arg-max (lowest index on ties) and log-sum-exp.
+// Philox4x32-10 (Salmon et al., SC'11): first output word for counter (c0, c1, c2, c3) under key (k0, k1).
+__device__ __forceinline__ uint32_t philox4x32_10_word0(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                                       uint32_t k1) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    c0 = hi1 ^ c1 ^ k0;
+    c1 = lo1;
+    c2 = hi0 ^ c3 ^ k1;
+    c3 = lo0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  return c0;
+}
+
+// Per row of fp32 logits: the emitted-token candidate and a log-sum-exp.
+//   greedy (inv_temp == 0): arg-max with the lowest index on ties, lse of the logits;
+//   sampling: Gumbel-max draw from softmax(logits * inv_temp) -- argmax_j logits_j * inv_temp - log(-log u_j), with
+//   u_j from Philox4x32-10 at counter (j, token index, seq_id) under the sample seed -- and the lse of the scaled logits.
 __global__ __launch_bounds__(1024) void k_argmax_lse(const float* __restrict__ logits, int V, int* __restrict__ row_argmax,
-                                                     float* __restrict__ row_lse) {
+                                                     float* __restrict__ row_lse, float inv_temp,
+                                                     unsigned long long seed, const int* __restrict__ row_slot,
+                                                     const int* __restrict__ slot_seq,
+                                                     const unsigned long long* __restrict__ seq_id,
+                                                     const int* __restrict__ seq_gen_len) {
   __shared__ float s_val[16];
   __shared__ int s_idx[16];
   __shared__ float s_sum[16];
+  __shared__ float s_max[16];
   const float* x = logits + (size_t)blockIdx.x * V;
-  float best = -INFINITY;
+  const bool sampling = inv_temp > 0.f;
+  const float scale = sampling ? inv_temp : 1.f;
+  uint32_t c1 = 0, c2 = 0, c3 = 0;
+  if (sampling) {
+    const int sidx = slot_seq[row_slot[blockIdx.x]];
+    const unsigned long long id = seq_id[sidx];
+    c1 = (uint32_t)seq_gen_len[sidx];
+    c2 = (uint32_t)id;
+    c3 = (uint32_t)(id >> 32);
+  }
+  const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+  float best = -INFINITY, mx = -INFINITY;
   int bi = 0x7fffffff;
   for (int i = threadIdx.x; i < V; i += 1024) {
-    const float v = x[i];
+    const float z = x[i] * scale;
+    mx = fmaxf(mx, z);
+    float v = z;
+    if (sampling) {
+      const float u = ((float)(philox4x32_10_word0((uint32_t)i, c1, c2, c3, k0, k1) >> 8) + 0.5f) * 5.9604644775390625e-8f;
+      v = z - __logf(-__logf(u));
+    }
     if (v > best) { best = v; bi = i; }       // strided ascending: first hit is the lowest index per thread
   }
 #pragma unroll
@@ -137,15 +179,18 @@ __global__ __launch_bounds__(1024) void k_argmax_lse(const float* __restrict__ l
     const float ov = __shfl_xor(best, o, 64);
     const int oi = __shfl_xor(bi, o, 64);
     if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+    mx = fmaxf(mx, __shfl_xor(mx, o, 64));
   }
   const int w = threadIdx.x >> 6;
-  if ((threadIdx.x & 63) == 0) { s_val[w] = best; s_idx[w] = bi; }
+  if ((threadIdx.x & 63) == 0) { s_val[w] = best; s_idx[w] = bi; s_max[w] = mx; }
   __syncthreads();
-  best = s_val[0]; bi = s_idx[0];
-  for (int k = 1; k < 16; ++k)
+  best = s_val[0]; bi = s_idx[0]; mx = s_max[0];
+  for (int k = 1; k < 16; ++k) {
     if (s_val[k] > best || (s_val[k] == best && s_idx[k] < bi)) { best = s_val[k]; bi = s_idx[k]; }
+    mx = fmaxf(mx, s_max[k]);
+  }
   float sum = 0.f;
-  for (int i = threadIdx.x; i < V; i += 1024) sum += __expf(x[i] - best);
+  for (int i = threadIdx.x; i < V; i += 1024) sum += __expf(x[i] * scale - mx);
   sum = wave_sum(sum);
   if ((threadIdx.x & 63) == 0) s_sum[w] = sum;
   __syncthreads();
@@ -153,7 +198,7 @@ __global__ __launch_bounds__(1024) void k_argmax_lse(const float* __restrict__ l
     float t = 0.f;
     for (int k = 0; k < 16; ++k) t += s_sum[k];
     row_argmax[blockIdx.x] = bi;
-    row_lse[blockIdx.x] = best + __logf(t);
+    row_lse[blockIdx.x] = mx + __logf(t);
   }
 }
 
@@ -235,8 +280,11 @@ void launch_rope_kvwrite(const float* part, int S, size_t part_stride, const flo
     hipLaunchKernelGGL(k_rope_kvwrite, dim3(R), dim3(1024), 0, st, part, S, part_stride, bias, row_slot, row_pos,
                        (const float2*)cs_table, (uint16_t*)q_out, (uint8_t*)pool, page_table, max_pages, Hq, Hkv, d);
 }
-void launch_argmax_lse(const float* logits, int V, int* row_argmax, float* row_lse, int R, hipStream_t st) {
-  if (R > 0) hipLaunchKernelGGL(k_argmax_lse, dim3(R), dim3(1024), 0, st, logits, V, row_argmax, row_lse);
+void launch_argmax_lse(const float* logits, int V, int* row_argmax, float* row_lse, int R, const SchedDev* sched,
+                       hipStream_t st) {
+  if (R > 0)
+    hipLaunchKernelGGL(k_argmax_lse, dim3(R), dim3(1024), 0, st, logits, V, row_argmax, row_lse, sched->inv_temp,
+                       sched->sample_seed, sched->row_slot, sched->slot_seq, sched->seq_id, sched->seq_gen_len);
 }
 void launch_gather_rows(const float* src, const int* src_row, float* dst, int dst_row0, int n, int D, hipStream_t st) {
   if (n > 0) hipLaunchKernelGGL(k_gather_rows, dim3(n), dim3(256), 0, st, src, src_row, dst, dst_row0, D);

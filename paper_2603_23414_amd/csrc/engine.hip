@@ -388,7 +388,7 @@ int step_impl(rollout_ctx* c, const int32_t* forced_tok, float* logits_out, roll
     if (n_adm > 0) TRY(run_prefill(c, n_dec, n_adm));
     launch_add_rmsnorm(c->h_final, nullptr, 0, 0, c->final_norm, c->cfg.rms_eps, c->x_final, n_rows, c->D, st);
     launch_gemm(c->x_final, c->lm_head, c->logits, n_rows, c->V, c->D, 1, st);
-    launch_argmax_lse(c->logits, c->V, c->row_argmax, c->row_lse, n_rows, st);
+    launch_argmax_lse(c->logits, c->V, c->row_argmax, c->row_lse, n_rows, &c->sd, st);
   }
   launch_sched_emit(c->sd, st);
   TRY(sync_status(c));
@@ -450,6 +450,7 @@ int rollout_init(rollout_ctx** out, const void* weights, size_t weights_bytes, c
     return fail(nullptr, ROLLOUT_EINVAL, "max_prompt_len, max_new_tokens and max_seqs must be positive");
   if (f.eos_id < 0 || (uint32_t)f.eos_id >= f.vocab) return fail(nullptr, ROLLOUT_EINVAL, "eos_id outside the vocabulary");
   if (f.mode > 2 || f.eos_mode > 1 || f.weight_dtype > 1) return fail(nullptr, ROLLOUT_EINVAL, "bad mode / eos_mode / weight_dtype");
+  if (!(f.temperature >= 0.f)) return fail(nullptr, ROLLOUT_EINVAL, "temperature must be >= 0");
   int ndev = 0;
   if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0 || f.device < 0 || f.device >= ndev)
     return fail(nullptr, ROLLOUT_EDEVICE, "no usable HIP device (this library has no CPU fallback)");
@@ -520,6 +521,7 @@ int rollout_init(rollout_ctx** out, const void* weights, size_t weights_bytes, c
   s.tok_stride = f.max_prompt_len + f.max_new_tokens; s.cap = f.max_new_tokens; s.eos_id = f.eos_id;
   s.eos_mode = f.eos_mode; s.mode = f.mode; s.max_staleness = f.max_staleness;
   s.no_model = (f.debug_flags & ROLLOUT_DEBUG_NO_MODEL) ? 1 : 0; s.V = c->V; s.Hkv = c->Hkv;
+  s.inv_temp = f.temperature > 0.f ? 1.0f / f.temperature : 0.f; s.sample_seed = f.sample_seed;
   const size_t MS = f.max_seqs, Q = c->Q;
   INIT_TRY(dev_alloc(c, &s.sc, SC_COUNT));
   INIT_TRY(dev_alloc(c, &s.ctr, CT_COUNT));

@@ -43,6 +43,7 @@ void launch_gemm_swiglu(const void* A, const void* W, void* act, int M, int N, i
 void launch_pack_weights(const void* src, void* dst, size_t N, size_t K, hipStream_t st);
 void launch_reduce_splits(const float* part, float* c, size_t mn, int S, hipStream_t st);
 
+struct SchedDev;
 // ---- fused small kernels ------------------------------------------------------------------------------
 void launch_embed(const void* table, const int* row_tok, float* h, int R, int D, hipStream_t st);
 void launch_add_rmsnorm(float* h, const float* part, int S, size_t part_stride, const float* gain, float eps, void* x,
@@ -50,7 +51,9 @@ void launch_add_rmsnorm(float* h, const float* part, int S, size_t part_stride, 
 void launch_rope_kvwrite(const float* part, int S, size_t part_stride, const float* bias, const int* row_slot,
                          const int* row_pos, const void* cs_table, void* q_out, void* pool, const int* page_table,
                          int max_pages, int Hq, int Hkv, int d, int R, hipStream_t st);
-void launch_argmax_lse(const float* logits, int V, int* row_argmax, float* row_lse, int R, hipStream_t st);
+// greedy (inv_temp == 0) or Gumbel-max sampling; row_lse is the log-sum-exp of logits * inv_temp (of logits if greedy)
+void launch_argmax_lse(const float* logits, int V, int* row_argmax, float* row_lse, int R, const SchedDev* sched,
+                       hipStream_t st);
 void launch_gather_rows(const float* src, const int* src_row, float* dst, int dst_row0, int n, int D, hipStream_t st);
 
 // ---- scheduler state (device side of the rollout state manager / stateful buffer, Sec. 3.3) ----------
@@ -69,6 +72,8 @@ enum {  // int cells of the status block copied to the host after every schedule
 
 struct SchedDev {
   int Q, max_pages, n_pages, max_seqs, qmask, tok_stride, cap, eos_id, eos_mode, mode, max_staleness, no_model, V, Hkv;
+  float inv_temp;          // 1 / temperature, 0 = greedy
+  unsigned long long sample_seed;
   int* sc;
   unsigned long long* ctr;
   int *slot_seq, *slot_npages, *page_table;

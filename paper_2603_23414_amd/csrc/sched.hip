@@ -208,7 +208,8 @@ __global__ __launch_bounds__(1024) void k_sched_emit(SchedDev d) {
     const bool forced = tgt > 0 && g + 1 == tgt;
     int tok = forced ? d.eos_id : (d.no_model ? 0 : d.row_argmax[r]);
     if (d.forced_tok && d.forced_tok[t] >= 0) tok = d.forced_tok[t];
-    const float lp = d.no_model ? 0.f : d.logits[(size_t)r * d.V + tok] - d.row_lse[r];
+    const float lscale = d.inv_temp > 0.f ? d.inv_temp : 1.f;   // log-prob under the distribution that was sampled
+    const float lp = d.no_model ? 0.f : d.logits[(size_t)r * d.V + tok] * lscale - d.row_lse[r];
     d.seq_tokens[(size_t)sidx * d.tok_stride + P + g] = tok;
     d.seq_logp[(size_t)sidx * d.cap + g] = lp;
     ++g;

@@ -14,7 +14,7 @@ def n_pages_for(shape, max_slots, max_prompt_len, cap, kv_pool_bytes=0, page_tok
 
 
 def make_oracle(shape, *, max_slots, max_prompt_len, cap, kv_pool_bytes=0, eos_mode=0, mode=0, max_staleness=-1,
-                page_seed=0, weights_blob=None, dtype=np.float64):
+                page_seed=0, weights_blob=None, dtype=np.float64, temperature=0.0, sample_seed=0):
     from oracle import OracleModel, OracleRollout, PagedKV
     n_pages = n_pages_for(shape, max_slots, max_prompt_len, cap, kv_pool_bytes)
     model = pool = None
@@ -24,15 +24,17 @@ def make_oracle(shape, *, max_slots, max_prompt_len, cap, kv_pool_bytes=0, eos_m
         pool = PagedKV(shape.n_layers, n_pages, 16, shape.n_kv_heads, shape.head_dim, dtype)
     return OracleRollout(max_slots=max_slots, page_tokens=16, n_pages=n_pages, max_new_tokens=cap,
                          eos_id=shape.vocab - 1, eos_mode=eos_mode, mode=mode, max_staleness=max_staleness,
-                         page_seed=page_seed, model=model, kv_pool=pool)
+                         page_seed=page_seed, model=model, kv_pool=pool, temperature=temperature,
+                         sample_seed=sample_seed)
 
 
 def make_engine(shape, weights_blob, *, max_slots, max_prompt_len, cap, max_seqs, kv_pool_bytes=0, eos_mode=0,
-                mode=0, max_staleness=-1, page_seed=0, debug_flags=0):
+                mode=0, max_staleness=-1, page_seed=0, debug_flags=0, temperature=0.0, sample_seed=0):
     import paper_2603_23414_amd as R
     cfg = R.make_cfg(shape, max_slots=max_slots, max_prompt_len=max_prompt_len, max_new_tokens=cap,
                      max_seqs=max_seqs, kv_pool_bytes=kv_pool_bytes, eos_mode=eos_mode, mode=mode,
-                     max_staleness=max_staleness, page_seed=page_seed, debug_flags=debug_flags)
+                     max_staleness=max_staleness, page_seed=page_seed, debug_flags=debug_flags,
+                     temperature=temperature, sample_seed=sample_seed)
     if weights_blob is None:
         weights_blob = np.zeros(1, np.uint16)
     return R.rollout_init(weights_blob, cfg)

@@ -246,6 +246,58 @@ def test_tiny_policy_free_running_is_deterministic_and_matches_schedule():
     assert [r[:4] for r in runs[0]] == ref
 
 
+def test_temperature_sampling_matches_the_oracle_sampler_on_the_engine_logits():
+    """Free-running sampled rollout (T = 0.8).  The schedule is length-forced, so the integer oracle tells which
+    sequence sits in which slot; the oracle's Gumbel-max sampler applied to the ENGINE's logits row must pick the
+    engine's token (a different pick is accepted only when the two best perturbed scores are a rounding apart), and the
+    recorded log-prob must be log softmax(logits / T) of that token."""
+    import paper_2603_23414_amd as R
+    from oracle import log_prob_at, perturbed_scores
+    c = W.CONFIGS["tiny"]
+    m = c.model
+    T, seed = 0.8, 0xC0FFEE1234
+    blob = W.make_weights(m, c.seed_weights)
+    prompts = [W.make_prompts(1, c.prompt_len, m.vocab, 5)[0]] * 6          # six responses to one prompt
+    L = W.make_target_lengths(6, c.len_mu, c.len_sigma, c.cap, 8)
+    orc = make_oracle(m, max_slots=4, max_prompt_len=c.prompt_len, cap=c.cap)    # integer schedule only
+    ctx = make_engine(m, blob, max_slots=4, max_prompt_len=c.prompt_len, cap=c.cap, max_seqs=6, temperature=T,
+                      sample_seed=seed)
+    try:
+        toks, offs = flat_prompts(prompts)
+        R.rollout_submit(ctx, toks, offs, L)
+        orc.submit(prompts, L)
+        logits = np.zeros((4, m.vocab), np.float32)
+        none = np.full(4, -1, np.int32)
+        checked = mismatched = 0
+        final = {}
+        while orc.queue or any(x is not None for x in orc.slots):
+            before = [s.gen_len for s in orc.seqs]
+            io = orc.step()
+            ig = R.rollout_step_forced(ctx, none, logits)
+            assert info_tuple(ig) == info_tuple(io)
+            for s in orc.seqs:
+                if s.gen_len > before[s.seq_id]:
+                    t = before[s.seq_id]
+                    tk, lp, state, slot = R.rollout_peek(ctx, s.seq_id, c.cap)
+                    assert len(tk) == t + 1
+                    final[s.seq_id] = tk.copy()
+                    row = logits[s.last_slot].astype(np.float64)
+                    if t + 1 == s.target_len:
+                        assert tk[t] == m.vocab - 1
+                        continue
+                    sc = perturbed_scores(row, T, seed, s.seq_id, t)
+                    checked += 1
+                    if int(np.argmax(sc)) != int(tk[t]):
+                        top2 = np.sort(sc)[-2:]
+                        assert top2[1] - top2[0] < 1e-3 and sc[tk[t]] >= top2[0] - 1e-6
+                        mismatched += 1
+                    assert abs(lp[t] - log_prob_at(row, int(tk[t]), T)) < 2e-4
+        assert checked > 50 and mismatched <= 1
+        assert len({tuple(v[:3]) for v in final.values()}) > 1       # the six responses are not all alike
+    finally:
+        R.rollout_destroy(ctx)
+
+
 def test_error_paths():
     import paper_2603_23414_amd as R
     c = W.CONFIGS["tiny"]
