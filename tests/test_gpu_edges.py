@@ -45,7 +45,7 @@ def test_natural_eos_and_cap_finish_rollouts():
     the prompts (they end on natural EOS or at the cap), under teacher forcing."""
     import paper_2603_23414_amd as R
     m = W.ModelShape(1, 64, 2, 2, 32, 64, 64, 1e-5, 1e4, 0)
-    blob = W.make_weights(m, 3, std=0.3)
+    blob = W.make_weights(m, 5, std=0.1)        # 5x the usual weight scale: EOS wins the argmax now and then
     g = W.rng(4)
     prompts = [g.integers(0, m.vocab - 1, int(k)).astype(np.int32) for k in g.integers(1, 20, 12)]
     L = np.array([0, 7, 0, 0, 12, 0, 3, 0, 0, 1, 0, 0], np.uint32)
@@ -56,7 +56,8 @@ def test_natural_eos_and_cap_finish_rollouts():
         R.rollout_submit(ctx, toks, offs, L)
         orc.submit(prompts, L)
         flat, recs, tok, worst = _lockstep(R, ctx, orc, 3, 4, m.vocab, True)
-        assert len(flat) == 12 and worst < 2e-2 * 8          # std 0.3 weights: logits ~15x the usual scale
+        # bf16 rounding error is relative, so the 2e-2 bound (stated at weight std 0.02) scales with the logits: x5
+        assert len(flat) == 12 and worst < 2e-2 * 5, worst
         natural = capped = 0
         for s, r, t in zip(flat, recs, tok):
             assert (r.seq_id, r.gen_len, r.completion_step, r.slot) == (s.seq_id, s.gen_len, s.completion_step, s.last_slot)
