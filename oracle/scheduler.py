@@ -24,7 +24,12 @@ step at a time, in plain Python with no batching tricks:
   sync baseline     -- a batch is admitted only when every slot is empty
                        (the canonical pipeline the paper compares against);
   bubble ratio      -- eq. 4 with one decode step as the time unit:
-                       sum_s (Q - r_s) / (Q * steps).
+                       sum_s (Q - r_s) / (Q * steps);
+  responses/prompt  -- the training recipe draws several responses per prompt
+                       (Sec. 4.1); `submit(..., n_responses=k)` makes k rollouts
+                       of one prompt that share the KV pages the prompt fills
+                       completely (all but the page holding its last token), so
+                       only the first of them to be admitted prefills the prompt.
 
 Readings where the paper is silent (slot choice, page allocation order, the
 preemption victim, the staleness rule) are this build's and are listed in the
@@ -66,6 +71,18 @@ def splitmix64_permutation(n: int, seed: int) -> List[int]:
     return perm
 
 
+class PromptGroup:
+    """The k rollouts of one prompt and the KV pages they share: the first `nshared` logical pages, which hold
+    prompt positions 0 .. 16*nshared-1 only (the page with the last prompt token is private, every rollout appends
+    its own tokens there).  `ref` counts the running rollouts attached; the pages return to the pool with the last."""
+
+    def __init__(self, nshared: int):
+        self.nshared = nshared
+        self.ref = 0
+        self.pages: List[int] = []
+        self.version = 0
+
+
 class Seq:
     """One entry of the stateful rollout buffer (Sec. 3.3): prompt context, partial
     trajectory, log-probs, completion flag (state) and lifecycle indicator (kv_version)."""
@@ -84,6 +101,8 @@ class Seq:
         self.pages: List[int] = []
         self.needs_prefill = True
         self.last_slot = -1       # slot of the most recent admission (reported at harvest)
+        self.group: Optional[PromptGroup] = None
+        self.prefill_from = 0     # first position the pending prefill computes (> 0: attached to shared pages)
 
     @property
     def gen_len(self) -> int:
@@ -125,19 +144,34 @@ class OracleRollout:
         self.last_logits = {}    # slot -> logits row of the last step (teacher-forcing parity)
 
     # ---- feed prompts (Fig. 2 step 1) ---------------------------------------------------
-    def submit(self, prompts: Sequence[np.ndarray], target_len: Sequence[int]) -> int:
+    def submit(self, prompts: Sequence[np.ndarray], target_len: Sequence[int], n_responses: int = 1) -> int:
+        """target_len has len(prompts) * n_responses entries, prompt-major; seq ids follow that order."""
         first = len(self.seqs)
-        for p, L in zip(prompts, target_len):
-            s = Seq(len(self.seqs), p, L)
-            self.seqs.append(s)
-            self.queue.append(s)
+        k = n_responses
+        assert len(target_len) == len(prompts) * k
+        for i, p in enumerate(prompts):
+            nshared = (len(p) - 1) // self.pt
+            grp = PromptGroup(nshared) if k > 1 and nshared > 0 else None
+            for r in range(k):
+                s = Seq(len(self.seqs), p, target_len[i * k + r])
+                s.group = grp
+                self.seqs.append(s)
+                self.queue.append(s)
         return first
 
     def _pages_for(self, n_tokens: int) -> int:
         return (n_tokens + self.pt - 1) // self.pt
 
     def _release(self, s: Seq) -> None:
-        for p in s.pages:             # ascending logical-page order
+        g = s.group
+        keep = 0
+        if g is not None:
+            g.ref -= 1
+            if g.ref > 0:
+                keep = g.nshared      # siblings still read the shared pages
+            else:
+                g.pages = []
+        for p in s.pages[keep:]:      # ascending logical-page order
             self.free.append(p)
         s.pages = []
         self.slots[s.slot] = None
@@ -162,15 +196,29 @@ class OracleRollout:
             if not free_slots:
                 break
             head: Seq = self.queue[0]
-            need = self._pages_for(len(head.prompt) + head.gen_len + 1)
+            g = head.group
+            attach = g is not None and g.ref > 0          # a sibling is running: its prompt pages are reused
+            need = self._pages_for(len(head.prompt) + head.gen_len + 1) - (g.nshared if attach else 0)
             if len(self.free) < need + reserve:
                 break
             self.queue.popleft()
             head.slot = head.last_slot = free_slots[0]
             self.slots[head.slot] = head
-            head.pages = [self.free.pop() for _ in range(need)]
+            fresh = [self.free.pop() for _ in range(need)]
+            if attach:
+                head.pages = list(g.pages) + fresh
+                head.kv_version = g.version               # its cache is as old as the shared part
+                head.prefill_from = g.nshared * self.pt
+            else:
+                head.pages = fresh
+                head.kv_version = self.version
+                head.prefill_from = 0
+                if g is not None:
+                    g.pages = fresh[:g.nshared]
+                    g.version = self.version
+            if g is not None:
+                g.ref += 1
             head.state = ACTIVE
-            head.kv_version = self.version
             head.needs_prefill = True
             admitted.append(head)
         self.max_pages_used = max(self.max_pages_used, self.n_pages - len(self.free))
@@ -182,9 +230,10 @@ class OracleRollout:
         for s in ran:
             if s.needs_prefill:
                 toks = s.prompt + s.tokens
-                self.prefill_tokens += len(toks)
+                p0 = s.prefill_from
+                self.prefill_tokens += len(toks) - p0
                 if self.model is not None:
-                    logits_of[s.slot] = self.model.run_tokens(toks, 0, self.kv_pool.view(s.pages))
+                    logits_of[s.slot] = self.model.run_tokens(toks[p0:], p0, self.kv_pool.view(s.pages))
                 s.needs_prefill = False
             elif self.model is not None:
                 pos = self._next_pos(s)

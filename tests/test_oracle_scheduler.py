@@ -294,3 +294,105 @@ def test_update_weights_same_policy_changes_nothing_and_new_policy_takes_over():
                 assert s.logp[t] == b.logp[t]
         changed += int(s.tokens != b.tokens)
     assert changed > 0
+
+
+# ---- several responses per prompt sharing the prompt's full KV pages ------------------------------------------------
+
+def test_shared_prompt_pages_hand_built():
+    """16-token pages, one prompt of 40 tokens (pages 0 and 1 hold prompt tokens only -> shared; page 2 holds
+    positions 32..47 -> private), 3 responses with L = 2, 5, 3, two slots, 8 pages.  The free list is a stack whose
+    top is the END of the splitmix64 permutation.
+      step 0: response 0 takes the top three pages and prefills 40 tokens; response 1 attaches: one new page,
+              prefill of positions 32..39 only (8 tokens).  4 pages free.
+      step 1: response 0 emits its forced EOS and leaves; pages 0, 1 stay (response 1 reads them), its page 2 returns.
+      step 2: response 2 takes slot 0, attaches, and gets that same page back; prefill 8 tokens.
+      the last one to leave returns the shared pages first, then its own."""
+    perm = splitmix64_permutation(8, 0)
+    o = OracleRollout(max_slots=2, page_tokens=16, n_pages=8, max_new_tokens=100, eos_id=99)
+    o.submit([np.arange(40, dtype=np.int32)], [2, 5, 3], n_responses=3)
+    o.step()
+    s0, s1, s2 = o.seqs
+    assert s0.pages == [perm[7], perm[6], perm[5]] and s1.pages == [perm[7], perm[6], perm[4]]
+    assert (s0.prefill_from, s1.prefill_from) == (0, 32) and o.prefill_tokens == 48 and len(o.free) == 4
+    o.step()
+    assert s0.completion_step == 1 and o.free == perm[:4] + [perm[5]]
+    o.step()
+    assert s2.last_slot == 0 and s2.pages == [perm[7], perm[6], perm[5]] and o.prefill_tokens == 56
+    o.run_to_completion(3)
+    # response 2 (L = 3) ends at step 4 and returns its private page; response 1 (L = 5) ends at step 4 too --
+    # higher slot, so it leaves last and returns the shared pages first, then its own
+    assert (s1.completion_step, s2.completion_step) == (4, 4)
+    assert o.free == perm[:4] + [perm[5], perm[7], perm[6], perm[4]]
+    assert o.stats()["max_pages_used"] == 4
+
+
+def test_shared_prompt_pages_give_the_same_rollouts_as_separate_copies_of_the_prompt():
+    """Attaching to a sibling's prompt pages must change no number: tokens, log-probs, completion steps and harvest
+    order equal those of the same prompts submitted k times without sharing; only the prefill work shrinks, by
+    16 * nshared tokens for every admission that attached."""
+    m, model = _tiny_model(5)
+    g = np.random.default_rng(2)
+    prompts = [g.integers(0, 11, n).astype(np.int32) for n in (9, 4, 13, 8, 5)]      # 4-token pages: nshared 2,0,3,1,1
+    k = 3
+    L = [int(x) for x in g.integers(1, 12, len(prompts) * k)]
+
+    def run(shared):
+        pool = PagedKV(1, 200, 4, 2, 8, np.float64)
+        o = OracleRollout(max_slots=4, page_tokens=4, n_pages=200, max_new_tokens=12, eos_id=11, model=model,
+                          kv_pool=pool, temperature=0.8, sample_seed=7)
+        if shared:
+            o.submit(prompts, L, n_responses=k)
+        else:
+            o.submit([p for p in prompts for _ in range(k)], L)
+        groups = o.run_to_completion(4)
+        return o, [[s.seq_id for s in gr] for gr in groups]
+
+    a, ga = run(True)
+    b, gb = run(False)
+    assert ga == gb
+    for x, y in zip(a.seqs, b.seqs):
+        assert x.tokens == y.tokens and x.logp == y.logp and x.completion_step == y.completion_step
+    assert len({tuple(s.tokens) for s in a.seqs[:3]}) > 1          # sampled siblings differ from one another
+    saved = b.prefill_tokens - a.prefill_tokens
+    assert saved > 0 and saved % 4 == 0
+    assert a.stats()["max_pages_used"] < b.stats()["max_pages_used"]
+
+
+@pytest.mark.parametrize("mode,stale", [(MODE_PARTIAL, -1), (MODE_PARTIAL, 1), (MODE_ONPOLICY, -1)])
+def test_shared_prompt_pages_are_conserved_under_preemption_staleness_and_termination(mode, stale):
+    """Every page is in exactly one place at every step: the free list, a group's shared set (counted once however
+    many rollouts read it) or one rollout's private tail; a group's count of readers equals its running rollouts."""
+    g = np.random.default_rng(11)
+    prompts = [g.integers(0, 50, int(n)).astype(np.int32) for n in g.integers(1, 30, 12)]
+    k = 4
+    L = _lengths(len(prompts) * k, 8, cap=60)
+    n_pages = 42
+    o = OracleRollout(max_slots=6, page_tokens=4, n_pages=n_pages, max_new_tokens=60, eos_id=99, mode=mode,
+                      max_staleness=stale)
+    o.submit(prompts, L, n_responses=k)
+    saw_share = 0
+    while o.queue or any(x is not None for x in o.slots):
+        o.step()
+        live = [s for s in o.slots if s is not None]
+        groups = {id(s.group): s.group for s in o.seqs if s.group is not None}
+        shared = [p for gr in groups.values() for p in gr.pages]
+        private = []
+        for s in live:
+            ns = s.group.nshared if s.group is not None else 0
+            if s.group is not None:
+                assert s.pages[:ns] == s.group.pages
+            private += s.pages[ns:]
+            assert (len(s.prompt) + s.gen_len - 1) // 4 < len(s.pages)
+        for gr in groups.values():
+            n_live = sum(1 for s in live if s.group is gr)
+            assert gr.ref == n_live and (len(gr.pages) == gr.nshared if n_live else gr.pages == [])
+            saw_share += int(n_live > 1)
+        everything = shared + private + o.free
+        assert len(everything) == n_pages and len(set(everything)) == n_pages
+        if len(o.finished) >= 5:
+            o.harvest(5)
+    o.harvest(5, flush=True)
+    assert saw_share > 0 and sorted(o.free) == list(range(n_pages))
+    assert all(s.state == HARVESTED for s in o.seqs) and [s.gen_len for s in o.seqs] == list(L)
+    if mode == MODE_PARTIAL and stale < 0:
+        assert o.n_preempt > 0                                         # the pool is small enough to preempt
