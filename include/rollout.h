@@ -141,6 +141,18 @@ int rollout_update_weights(rollout_ctx*, const void* weights, size_t weights_byt
 int rollout_submit(rollout_ctx*, const int32_t* tokens, const uint32_t* offsets, const uint32_t* target_len,
                    uint32_t n, uint64_t* first_seq_id);
 
+/* Sec. 4.1 (several responses are drawn for every prompt): like rollout_submit, but each of the n prompts starts k
+ * rollouts.  target_len has n*k entries, prompt-major; seq ids follow the same order (prompt i, response r ->
+ * first_seq_id + i*k + r).  The k rollouts of a prompt share the KV pages the prompt fills completely, except the page
+ * holding its last token: floor((prompt_len - 1) / 16) pages.  The first of them to be admitted allocates and
+ * prefills the whole prompt; one admitted while a sibling is running allocates only its private tail and prefills
+ * from the first unshared position; shared pages return to the pool when the last running sibling leaves (finish,
+ * preemption, staleness or on-policy termination), and a rollout that attached takes the shared part's policy
+ * version as its own for the staleness rule.  With temperature 0 the k responses are identical.  k = 1, or a prompt
+ * of at most 16 tokens, shares nothing.  Errors as rollout_submit; EINVAL for k = 0; n*k counts against max_seqs. */
+int rollout_submit_n(rollout_ctx*, const int32_t* tokens, const uint32_t* offsets, const uint32_t* target_len,
+                     uint32_t n, uint32_t k, uint64_t* first_seq_id);
+
 /* One global decode step (Sec. 3.1): refill free slots from the queue head (prefill), decode one token for
  * every other running request, emit (forced EOS / greedy argmax, lowest index on ties / a Gumbel-max draw when
  * cfg.temperature > 0: argmax_j logits_j / T - log(-log u_j), u_j from Philox4x32-10), evict finished

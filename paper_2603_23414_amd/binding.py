@@ -17,7 +17,7 @@ __all__ = [
     "rollout_attn_pool_bytes", "rollout_attn_write_kv", "rollout_attn_workspace_bytes", "rollout_attn_plan",
     "rollout_attn_decode", "rollout_gemm_workspace_bytes", "rollout_gemm_bf16", "rollout_stream_copy",
     "rollout_stream_read", "rollout_gemm_packed_bytes", "rollout_gemm_pack_weights", "rollout_update_weights",
-    "make_cfg",
+    "rollout_submit_n", "make_cfg",
     "ROLLOUT_FLUSH", "ROLLOUT_DEBUG_NO_MODEL", "ROLLOUT_DEBUG_TIME_ATTN", "ROLLOUT_MODE_PARTIAL",
     "ROLLOUT_MODE_ONPOLICY", "ROLLOUT_MODE_SYNC", "ROLLOUT_EOS_FORCED_ONLY", "ROLLOUT_EOS_NATURAL_OR_FORCED",
     "EXPORTS",
@@ -40,7 +40,7 @@ EXPORTS = [
     "rollout_peek", "rollout_slot_pages", "rollout_last_error", "rollout_destroy", "rollout_attn_pool_bytes",
     "rollout_attn_write_kv", "rollout_attn_workspace_bytes", "rollout_attn_plan", "rollout_attn_decode",
     "rollout_gemm_workspace_bytes", "rollout_gemm_bf16", "rollout_stream_copy", "rollout_stream_read",
-    "rollout_gemm_packed_bytes", "rollout_gemm_pack_weights", "rollout_update_weights",
+    "rollout_gemm_packed_bytes", "rollout_gemm_pack_weights", "rollout_update_weights", "rollout_submit_n",
 ]
 
 
@@ -85,6 +85,7 @@ _vp, _u32, _u64, _i32 = C.c_void_p, C.c_uint32, C.c_uint64, C.c_int32
 lib.rollout_init.argtypes = [C.POINTER(_vp), _vp, C.c_size_t, C.POINTER(rollout_cfg)]
 lib.rollout_update_weights.argtypes = [_vp, _vp, C.c_size_t]
 lib.rollout_submit.argtypes = [_vp, _vp, _vp, _vp, _u32, C.POINTER(_u64)]
+lib.rollout_submit_n.argtypes = [_vp, _vp, _vp, _vp, _u32, _u32, C.POINTER(_u64)]
 lib.rollout_step.argtypes = [_vp, C.POINTER(rollout_step_info)]
 lib.rollout_step_forced.argtypes = [_vp, _vp, _vp, C.POINTER(rollout_step_info)]
 lib.rollout_harvest.argtypes = [_vp, _u32, _u32, _vp, _u32, _vp, _vp, _u64, C.POINTER(_u32), C.POINTER(_u32),
@@ -173,6 +174,17 @@ def rollout_submit(ctx, tokens, offsets, target_len) -> int:
     first = _u64()
     _check(lib.rollout_submit(ctx, t.ctypes.data_as(_vp), o.ctypes.data_as(_vp), L.ctypes.data_as(_vp), len(L),
                               C.byref(first)), ctx)
+    return first.value
+
+
+def rollout_submit_n(ctx, tokens, offsets, target_len, k) -> int:
+    t, o, L = _np(tokens, np.int32), _np(offsets, np.uint32), _np(target_len, np.uint32)
+    n = len(o) - 1
+    if len(L) != n * k:
+        raise ValueError("target_len needs one entry per (prompt, response)")
+    first = _u64()
+    _check(lib.rollout_submit_n(ctx, t.ctypes.data_as(_vp), o.ctypes.data_as(_vp), L.ctypes.data_as(_vp), n, k,
+                                C.byref(first)), ctx)
     return first.value
 
 

@@ -34,6 +34,7 @@ struct SeqHost {
   int prompt_len = 0;
   bool in_use = false;
   bool harvested = false;
+  int group = -1;       // prompt-group table index (several responses of one prompt), -1 = none
 };
 
 }  // namespace
@@ -91,6 +92,8 @@ struct rollout_ctx {
   // host bookkeeping
   std::vector<SeqHost> seqs;
   std::vector<int> free_sidx;
+  std::vector<int> free_group;        // prompt-group table: free indices and unharvested members per group
+  std::vector<int> group_members;
   std::unordered_map<uint64_t, int> id2sidx;
   uint64_t next_seq_id = 0, n_submitted = 0, n_harvested = 0, n_groups_total = 0;
   // timing
@@ -316,14 +319,15 @@ void run_layers(rollout_ctx* c, int R, const int* row_slot, const int* row_pos, 
 }
 
 int run_prefill(rollout_ctx* c, int n_dec, int n_adm) {
-  // admitted sequences in ascending slot order: (slot, sidx, n_tok) triples in the status block
+  // admitted sequences in ascending slot order (= admission order, so a rollout that attaches to shared prompt
+  // pages always comes after the sibling that fills them): (slot, sidx, end position, first position) per admission
   const int* desc = c->status_host + STAT_HDR;
-  int a = 0, pos = 0;  // cursor: sequence a, next position pos
+  int a = 0, pos = desc[3];  // cursor: sequence a, next position pos
   hipStream_t st = c->stream;
   while (a < n_adm) {
     int rows = 0, n_desc = 0, n_last = 0, n_tiles = 0;
     while (a < n_adm && rows < PF_ROWS) {
-      const int slot = desc[3 * a], sidx = desc[3 * a + 1], n = desc[3 * a + 2];
+      const int slot = desc[STAT_ADM_INTS * a], sidx = desc[STAT_ADM_INTS * a + 1], n = desc[STAT_ADM_INTS * a + 2];
       const int take = std::min(n - pos, PF_ROWS - rows);
       c->pf_desc_host[n_desc++] = PrefillDesc{slot, sidx, take, pos, rows};
       for (int t = 0; t < take; t += 32)   // query tiles of up to 32 consecutive tokens
@@ -335,7 +339,7 @@ int run_prefill(rollout_ctx* c, int n_dec, int n_adm) {
         c->pf_last_host[2 * n_last + 1] = a;      // its index among the admitted
         ++n_last;
         ++a;
-        pos = 0;
+        pos = a < n_adm ? desc[STAT_ADM_INTS * a + 3] : 0;
       }
     }
     HIPCHK(c, hipMemcpyAsync(c->pf_desc_dev, c->pf_desc_host, sizeof(PrefillDesc) * n_desc, hipMemcpyHostToDevice, st));
@@ -539,6 +543,12 @@ int rollout_init(rollout_ctx** out, const void* weights, size_t weights_bytes, c
   INIT_TRY(dev_alloc(c, &s.seq_id, MS));
   INIT_TRY(dev_alloc(c, &s.seq_tokens, MS * s.tok_stride));
   INIT_TRY(dev_alloc(c, &s.seq_logp, MS * s.cap));
+  s.max_shared = std::max(1, (int)((f.max_prompt_len - 1) / PAGE_TOKENS));
+  INIT_TRY(dev_alloc(c, &s.seq_group, MS));
+  INIT_TRY(dev_alloc(c, &s.grp_nshared, MS));
+  INIT_TRY(dev_alloc(c, &s.grp_ref, MS));
+  INIT_TRY(dev_alloc(c, &s.grp_version, MS));
+  INIT_TRY(dev_alloc(c, &s.grp_pages, MS * (size_t)s.max_shared));
   INIT_TRY(dev_alloc(c, &s.q_ring, (size_t)qcap));
   INIT_TRY(dev_alloc(c, &s.free_stack, (size_t)c->n_pages));
   INIT_TRY(dev_alloc(c, &s.fin_list, MS));
@@ -548,7 +558,7 @@ int rollout_init(rollout_ctx** out, const void* weights, size_t weights_bytes, c
   INIT_TRY(dev_alloc(c, &s.row_wstart, Q));
   const size_t dec_work = Q * (size_t)((s.tok_stride + ATTN_CHUNK_MIN - 1) / ATTN_CHUNK_MIN);
   INIT_TRY(dev_alloc(c, &s.work, dec_work));
-  c->status_ints = STAT_HDR + 3 * c->Q;
+  c->status_ints = STAT_HDR + STAT_ADM_INTS * c->Q;
   INIT_TRY(dev_alloc(c, &s.status, (size_t)c->status_ints));
   INIT_TRY(host_alloc(c, &c->status_host, (size_t)c->status_ints));
   INIT_TRY(dev_alloc(c, &c->forced_tok_dev, Q));
@@ -560,6 +570,8 @@ int rollout_init(rollout_ctx** out, const void* weights, size_t weights_bytes, c
   launch_sched_init(s, c->stream);
   c->seqs.resize(MS);
   for (int i = (int)MS - 1; i >= 0; --i) c->free_sidx.push_back(i);
+  for (int i = (int)MS - 1; i >= 0; --i) c->free_group.push_back(i);
+  c->group_members.assign(MS, 0);
   INIT_TRY(host_alloc(c, &c->sub_host, MS));
   INIT_TRY(dev_alloc(c, &c->sub_dev, MS));
   INIT_TRY(host_alloc(c, &c->tok_stage_host, MS * f.max_prompt_len));
@@ -623,44 +635,64 @@ int rollout_init(rollout_ctx** out, const void* weights, size_t weights_bytes, c
 #undef INIT_HIP
 }
 
-int rollout_submit(rollout_ctx* c, const int32_t* tokens, const uint32_t* offsets, const uint32_t* target_len,
-                   uint32_t n, uint64_t* first_seq_id) {
+int rollout_submit_n(rollout_ctx* c, const int32_t* tokens, const uint32_t* offsets, const uint32_t* target_len,
+                     uint32_t n, uint32_t k, uint64_t* first_seq_id) {
   if (!c || !tokens || !offsets || (!target_len && n)) return fail(c, ROLLOUT_EINVAL, "null argument");
+  if (k == 0) return fail(c, ROLLOUT_EINVAL, "responses per prompt must be positive");
   if (c->dead) return fail(c, ROLLOUT_EDEVICE, "context unusable after an earlier device error");
   if (c->cfg.grouped_loading && c->n_submitted != c->n_harvested)
     return fail(c, ROLLOUT_EBUSY, "grouped loading: the previous group is not fully harvested");
-  if (n > c->free_sidx.size()) return fail(c, ROLLOUT_EBUSY, "sequence table full (max_seqs unharvested rollouts)");
+  const uint64_t total = (uint64_t)n * k;
+  if (total > c->free_sidx.size()) return fail(c, ROLLOUT_EBUSY, "sequence table full (max_seqs unharvested rollouts)");
   for (uint32_t i = 0; i < n; ++i) {
     if (offsets[i + 1] <= offsets[i] || offsets[i + 1] - offsets[i] > c->cfg.max_prompt_len)
       return fail(c, ROLLOUT_ERANGE, "empty or over-long prompt");
-    if (target_len[i] > c->cfg.max_new_tokens) return fail(c, ROLLOUT_ERANGE, "target_len exceeds max_new_tokens");
+    for (uint32_t r = 0; r < k; ++r)
+      if (target_len[(size_t)i * k + r] > c->cfg.max_new_tokens)
+        return fail(c, ROLLOUT_ERANGE, "target_len exceeds max_new_tokens");
     for (uint32_t j = offsets[i]; j < offsets[i + 1]; ++j)
       if (tokens[j] < 0 || (uint32_t)tokens[j] >= c->cfg.vocab) return fail(c, ROLLOUT_ERANGE, "token id outside the vocabulary");
   }
   if (first_seq_id) *first_seq_id = c->next_seq_id;
-  if (n == 0) return ROLLOUT_OK;
+  if (total == 0) return ROLLOUT_OK;
   HIPCHK(c, hipSetDevice(c->cfg.device));
-  size_t tok_off = 0;
+  size_t tok_off = 0, rec = 0;
   for (uint32_t i = 0; i < n; ++i) {
-    const int sidx = c->free_sidx.back();
-    c->free_sidx.pop_back();
     const int plen = (int)(offsets[i + 1] - offsets[i]);
-    SeqHost& sh = c->seqs[sidx];
-    sh.seq_id = c->next_seq_id++;
-    sh.prompt_len = plen;
-    sh.in_use = true;
-    sh.harvested = false;
-    c->id2sidx[sh.seq_id] = sidx;
-    c->sub_host[i] = SubmitRec{sidx, plen, (int)target_len[i], (int)tok_off, sh.seq_id};
+    // the pages a prompt fills completely, not counting the one with its last token, are shared by its responses
+    const int nshared = (plen - 1) / PAGE_TOKENS;
+    int group = -1;
+    if (k > 1 && nshared > 0) {
+      group = c->free_group.back();
+      c->free_group.pop_back();
+      c->group_members[group] = (int)k;
+    }
+    for (uint32_t r = 0; r < k; ++r) {
+      const int sidx = c->free_sidx.back();
+      c->free_sidx.pop_back();
+      SeqHost& sh = c->seqs[sidx];
+      sh.seq_id = c->next_seq_id++;
+      sh.prompt_len = plen;
+      sh.in_use = true;
+      sh.harvested = false;
+      sh.group = group;
+      c->id2sidx[sh.seq_id] = sidx;
+      c->sub_host[rec++] = SubmitRec{sidx, plen, (int)target_len[(size_t)i * k + r], (int)tok_off, sh.seq_id, group, nshared};
+    }
     memcpy(c->tok_stage_host + tok_off, tokens + offsets[i], sizeof(int) * plen);
     tok_off += plen;
   }
-  c->n_submitted += n;
-  HIPCHK(c, hipMemcpyAsync(c->sub_dev, c->sub_host, sizeof(SubmitRec) * n, hipMemcpyHostToDevice, c->stream));
+  c->n_submitted += total;
+  HIPCHK(c, hipMemcpyAsync(c->sub_dev, c->sub_host, sizeof(SubmitRec) * total, hipMemcpyHostToDevice, c->stream));
   HIPCHK(c, hipMemcpyAsync(c->tok_stage_dev, c->tok_stage_host, sizeof(int) * tok_off, hipMemcpyHostToDevice, c->stream));
-  launch_sched_submit(c->sd, c->sub_dev, c->tok_stage_dev, (int)n, c->stream);
+  launch_sched_submit(c->sd, c->sub_dev, c->tok_stage_dev, (int)total, c->stream);
   TRY(sync_status(c));
   return ROLLOUT_OK;
+}
+
+int rollout_submit(rollout_ctx* c, const int32_t* tokens, const uint32_t* offsets, const uint32_t* target_len,
+                   uint32_t n, uint64_t* first_seq_id) {
+  return rollout_submit_n(c, tokens, offsets, target_len, n, 1, first_seq_id);
 }
 
 int rollout_update_weights(rollout_ctx* c, const void* weights, size_t weights_bytes) {
@@ -690,7 +722,7 @@ int rollout_step_forced(rollout_ctx* c, const int32_t* forced_tok, float* logits
   if (r != 0) return r;
   if (c->cfg.debug_flags & ROLLOUT_DEBUG_NO_MODEL) return 0;
   const int n_adm = c->status_host[STAT_NADM];
-  for (int a = 0; a < n_adm; ++a) row_slot[n_dec + a] = c->status_host[STAT_HDR + 3 * a];
+  for (int a = 0; a < n_adm; ++a) row_slot[n_dec + a] = c->status_host[STAT_HDR + STAT_ADM_INTS * a];
   for (int row = 0; row < n_dec + n_adm; ++row)
     HIPCHK(c, hipMemcpy(logits_out + (size_t)row_slot[row] * c->V, c->logits + (size_t)row * c->V, sizeof(float) * c->V,
                         hipMemcpyDeviceToHost));
@@ -758,6 +790,8 @@ int rollout_harvest(rollout_ctx* c, uint32_t group_size, uint32_t flags, rollout
     c->seqs[sidx].in_use = false;
     c->id2sidx.erase(c->seqs[sidx].seq_id);
     c->free_sidx.push_back(sidx);
+    const int grp = c->seqs[sidx].group;
+    if (grp >= 0 && --c->group_members[grp] == 0) c->free_group.push_back(grp);
   }
   // remainder stays finished-unharvested, in its sorted order
   const int rest = nfin - take;

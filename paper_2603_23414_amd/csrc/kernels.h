@@ -68,7 +68,8 @@ enum {  // 64-bit counters in SchedDev::ctr
 enum {  // int cells of the status block copied to the host after every scheduler kernel
   STAT_STEP = 0, STAT_R, STAT_NACTIVE, STAT_FIN, STAT_QUEUED, STAT_FREE, STAT_NADM, STAT_NFIN_STEP, STAT_NPRE_STEP,
   STAT_NDEC_NEXT, STAT_NWORK_NEXT, STAT_CTX_LO, STAT_CTX_HI, STAT_VERSION, STAT_CHUNK, STAT_HDR = 16
-};  // followed by max_slots admission descriptors of 3 ints: slot, sequence-table index, tokens to prefill
+};  // followed by max_slots admission descriptors of STAT_ADM_INTS ints: slot, sequence-table index, end position
+#define STAT_ADM_INTS 4   // ... and the first position to prefill (> 0 when the rollout attached to shared prompt pages)
 
 struct SchedDev {
   int Q, max_pages, n_pages, max_seqs, qmask, tok_stride, cap, eos_id, eos_mode, mode, max_staleness, no_model, V, Hkv;
@@ -82,6 +83,11 @@ struct SchedDev {
   unsigned long long* seq_id;
   int* seq_tokens;
   float* seq_logp;
+  // prompt groups: the rollouts of one prompt share the pages the prompt fills completely (Sec. 4.1: several
+  // responses per prompt); grp_ref counts the running rollouts that read them
+  int *seq_group;          // group-table index or -1
+  int *grp_nshared, *grp_ref, *grp_version, *grp_pages;   // grp_pages: [max_seqs][max_shared]
+  int max_shared;
   int *q_ring, *free_stack, *fin_list;
   int *row_slot, *row_pos, *row_tok, *row_wstart;
   int2* work;
@@ -92,7 +98,7 @@ struct SchedDev {
   int* status;
 };
 
-struct SubmitRec { int sidx, prompt_len, target_len, tok_off; unsigned long long seq_id; };
+struct SubmitRec { int sidx, prompt_len, target_len, tok_off; unsigned long long seq_id; int group, nshared; };
 
 void launch_sched_admit(const SchedDev& d, hipStream_t st);
 void launch_sched_emit(const SchedDev& d, hipStream_t st);

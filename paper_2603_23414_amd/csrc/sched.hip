@@ -91,18 +91,36 @@ __device__ void rebuild_rows_and_status(const SchedDev& d, int* sh, int r_this_s
   }
 }
 
-// Release the pages and slot of every flagged slot, ascending slot order, pages in logical order.
-__device__ void release_flagged(const SchedDev& d, int* sh, bool flag) {
+// Release the slot and the pages of every flagged slot, ascending slot order, pages in logical order.  Shared
+// prompt pages stay with the group while another running rollout reads them; the last one to leave (the highest
+// flagged slot of the group, if that empties it) returns them, ahead of its own.  `grp_of` is 1024 ints of LDS.
+__device__ void release_flagged(const SchedDev& d, int* sh, int* grp_of, bool flag) {
   const int t = threadIdx.x;
-  const int npg = flag ? d.slot_npages[t] : 0;
+  int g = -1;
+  if (flag) g = d.seq_group[d.slot_seq[t]];
+  grp_of[t] = g;
+  __syncthreads();
+  int first = 0, leavers = 0;
+  bool highest = true;
+  if (g >= 0) {
+    for (int j = 0; j < d.Q; ++j)
+      if (grp_of[j] == g) {
+        ++leavers;
+        if (j > t) highest = false;
+      }
+    const bool last = highest && d.grp_ref[g] == leavers;
+    if (!last) first = d.grp_nshared[g];
+  }
+  const int npg = flag ? d.slot_npages[t] - first : 0;
   int freed;
   const int off = block_scan_excl(npg, &freed, sh);
   const int n_free0 = d.sc[SC_NFREE];
-  __syncthreads();
+  __syncthreads();                                 // every grp_ref read above precedes the update below
   if (flag) {
-    for (int j = 0; j < npg; ++j) d.free_stack[n_free0 + off + j] = d.page_table[(size_t)t * d.max_pages + j];
+    for (int j = 0; j < npg; ++j) d.free_stack[n_free0 + off + j] = d.page_table[(size_t)t * d.max_pages + first + j];
     d.slot_seq[t] = -1;
     d.slot_npages[t] = 0;
+    if (g >= 0 && highest) d.grp_ref[g] -= leavers;
   }
   __syncthreads();
   if (t == 0) d.sc[SC_NFREE] = n_free0 + freed;
@@ -113,7 +131,7 @@ __device__ void release_flagged(const SchedDev& d, int* sh, bool flag) {
 // plus the token it will emit; a reserve keeps this step's page growth from failing).
 __global__ __launch_bounds__(1024) void k_sched_admit(SchedDev d) {
   __shared__ int sh[20];
-  __shared__ int adm_slot[1024], adm_need[1024], adm_start[1024];
+  __shared__ int adm_slot[1024], adm_need[1024], adm_start[1024], adm_grp[1024], adm_first[1024];
   __shared__ int n_adm_sh;
   const int t = threadIdx.x;
   int need = 0, act = 0;
@@ -140,24 +158,35 @@ __global__ __launch_bounds__(1024) void k_sched_admit(SchedDev d) {
       if (cursor >= d.Q) break;
       const int sidx = d.q_ring[qh];
       const int n = d.seq_prompt_len[sidx] + d.seq_gen_len[sidx];
-      const int pages = (n + 1 + PAGE_TOKENS - 1) / PAGE_TOKENS;
+      const int total = (n + 1 + PAGE_TOKENS - 1) / PAGE_TOKENS;
+      // a running sibling's prompt pages are reused: only the private tail is allocated and prefilled
+      const int g = d.seq_group[sidx];
+      const int shared = (g >= 0 && d.grp_ref[g] > 0) ? d.grp_nshared[g] : 0;
+      const int pages = total - shared;
       if (n_free < pages + reserve) break;
       qh = (qh + 1) & d.qmask;
       --qc;
       d.slot_seq[cursor] = sidx;
-      d.slot_npages[cursor] = pages;
+      d.slot_npages[cursor] = total;
       d.seq_state[sidx] = SEQ_ACTIVE;
       d.seq_slot[sidx] = cursor;
-      d.seq_kv_version[sidx] = ver;
+      d.seq_kv_version[sidx] = shared ? d.grp_version[g] : ver;   // a cache is as old as its shared part
+      if (g >= 0) {
+        if (!shared) d.grp_version[g] = ver;
+        d.grp_ref[g] += 1;
+      }
       adm_slot[n_adm] = cursor;
       adm_need[n_adm] = pages;
       adm_start[n_adm] = n_free;
+      adm_grp[n_adm] = g;
+      adm_first[n_adm] = shared;
       n_free -= pages;
-      pf_tokens += n;
-      int* desc = d.status + STAT_HDR + 3 * n_adm;
+      pf_tokens += n - shared * PAGE_TOKENS;
+      int* desc = d.status + STAT_HDR + STAT_ADM_INTS * n_adm;
       desc[0] = cursor;
       desc[1] = sidx;
       desc[2] = n;
+      desc[3] = shared * PAGE_TOKENS;
       ++n_adm;
       ++cursor;
     }
@@ -175,9 +204,21 @@ __global__ __launch_bounds__(1024) void k_sched_admit(SchedDev d) {
   __syncthreads();
   const int n_adm = n_adm_sh;
   const int n_dec = d.sc[SC_NDEC];
-  for (int a = 0; a < n_adm; ++a)
-    for (int j = t; j < adm_need[a]; j += 1024)
-      d.page_table[(size_t)adm_slot[a] * d.max_pages + j] = d.free_stack[adm_start[a] - 1 - j];
+  for (int a = 0; a < n_adm; ++a) {
+    const int g = adm_grp[a], first = adm_first[a];
+    int* row = d.page_table + (size_t)adm_slot[a] * d.max_pages;
+    for (int j = t; j < adm_need[a]; j += 1024) row[first + j] = d.free_stack[adm_start[a] - 1 - j];
+    if (g >= 0) {                                     // uniform
+      int* gp = d.grp_pages + (size_t)g * d.max_shared;
+      if (first > 0) {
+        for (int j = t; j < first; j += 1024) row[j] = gp[j];
+      } else {                                        // first of its group to run: its leading pages become the shared set
+        const int ns = d.grp_nshared[g];
+        for (int j = t; j < ns; j += 1024) gp[j] = d.free_stack[adm_start[a] - 1 - j];
+      }
+      __syncthreads();                                // a later admission of this launch may attach to them
+    }
+  }
   if (t < n_adm) d.row_slot[n_dec + t] = adm_slot[t];
 }
 
@@ -185,7 +226,7 @@ __global__ __launch_bounds__(1024) void k_sched_admit(SchedDev d) {
 // empty), account the step, rebuild the row list for the next step.
 __global__ __launch_bounds__(1024) void k_sched_emit(SchedDev d) {
   __shared__ int sh[20];
-  __shared__ int slot_row[1024];
+  __shared__ int slot_row[1024], grp_of[1024];
   const int t = threadIdx.x;
   const int n_dec = d.sc[SC_NDEC], n_pre = d.sc[SC_NPRE];
   const int n_rows = n_dec + n_pre;
@@ -224,7 +265,7 @@ __global__ __launch_bounds__(1024) void k_sched_emit(SchedDev d) {
     d.seq_completion[my_sidx] = step;
     d.seq_state[my_sidx] = SEQ_FINISHED;
   }
-  release_flagged(d, sh, fin != 0);
+  release_flagged(d, sh, grp_of, fin != 0);
   if (t == 0) d.sc[SC_FINCOUNT] = fin0 + n_fin;
 
   // ---- D: page growth ---------------------------------------------------------------------------
@@ -267,7 +308,10 @@ __global__ __launch_bounds__(1024) void k_sched_emit(SchedDev d) {
           if (vs < 0 || g2 < vg || (g2 == vg && id2 > vid)) { vs = j; vg = g2; vid = id2; }
         }
         const int s2 = d.slot_seq[vs];
-        for (int j = 0; j < d.slot_npages[vs]; ++j) d.free_stack[nf++] = d.page_table[(size_t)vs * d.max_pages + j];
+        const int grp = d.seq_group[s2];
+        int first = 0;                                   // shared prompt pages stay while a sibling reads them
+        if (grp >= 0 && (d.grp_ref[grp] -= 1) > 0) first = d.grp_nshared[grp];
+        for (int j = first; j < d.slot_npages[vs]; ++j) d.free_stack[nf++] = d.page_table[(size_t)vs * d.max_pages + j];
         d.slot_seq[vs] = -1;
         d.slot_npages[vs] = 0;
         d.seq_state[s2] = SEQ_QUEUED;
@@ -312,6 +356,7 @@ __global__ __launch_bounds__(1024) void k_sched_emit(SchedDev d) {
 // rollout and discards its tokens.  Evicted rollouts go to the queue front in ascending seq_id.
 __global__ __launch_bounds__(1024) void k_sched_boundary(SchedDev d, int n_groups) {
   __shared__ int sh[20];
+  __shared__ int grp_of[1024];
   __shared__ unsigned long long ids[1024];
   const int t = threadIdx.x;
   const int ver = d.sc[SC_VERSION] + n_groups;
@@ -336,7 +381,7 @@ __global__ __launch_bounds__(1024) void k_sched_boundary(SchedDev d, int n_group
       d.seq_gen_len[sidx] = 0;
     }
   }
-  release_flagged(d, sh, out);
+  release_flagged(d, sh, grp_of, out);
   const int head0 = d.sc[SC_QHEAD];
   __syncthreads();
   const int new_head = (head0 - n_out) & d.qmask;
@@ -372,6 +417,12 @@ __global__ __launch_bounds__(256) void k_sched_submit_copy(SchedDev d, const Sub
     d.seq_kv_version[r.sidx] = 0;
     d.seq_npreempt[r.sidx] = 0;
     d.seq_id[r.sidx] = r.seq_id;
+    d.seq_group[r.sidx] = r.group;
+    if (r.group >= 0) {           // every sibling writes the same values
+      d.grp_nshared[r.group] = r.nshared;
+      d.grp_ref[r.group] = 0;
+      d.grp_version[r.group] = 0;
+    }
   }
 }
 __global__ void k_sched_submit_enqueue(SchedDev d, const SubmitRec* __restrict__ recs, int n) {
