@@ -3,8 +3,8 @@
 
 A step is one rollout_step() of the whole hot path (refill + prefill, decode of every running slot through all
 layers, LM head, argmax/EOS, eviction, page growth; harvest whenever a full update group is ready) on the
-8B-shaped, 16k-cap workload.  The timed window starts from a representative mid-run state: the integer
-scheduler (oracle, CPU, no model) is run to the step whose in-flight context is closest to the run's average,
+8B-shaped, 16k-cap workload.  The timed window starts from a representative mid-run state: the library's
+scheduler is first run alone (no model) to the step whose in-flight context is closest to the run's average,
 and that state is recreated through the public API by submitting each running rollout as prompt + already
 generated tokens (what partial mode re-feeds after an interruption); their prefill is warm-up.
 """
@@ -48,42 +48,57 @@ def device_weights(torch, m, seed):
     return blob
 
 
-def scheduler_snapshot(wl, L):
-    """Run the integer scheduler oracle over the whole workload; return (snapshot for the warm start, full-run stats)."""
-    from oracle import OracleRollout
-    from tests._util import n_pages_for
+def scheduler_snapshot(R, wl, L):
+    """Run the library's own scheduler without the model (ROLLOUT_DEBUG_NO_MODEL: same kernels, same page accounting,
+    milliseconds per thousand steps) over the whole workload; return (snapshot for the warm start, full-run stats)."""
     m = wl.model
-    n_pages = n_pages_for(m, wl.max_slots, wl.prompt_len, wl.cap, wl.kv_pool_bytes)
+    offs = np.arange(wl.n_prompts + 1, dtype=np.uint32) * wl.prompt_len
+    toks = np.zeros(wl.n_prompts * wl.prompt_len, np.int32)
 
     def mk(mode=0, stale=wl.max_staleness):
-        o = OracleRollout(max_slots=wl.max_slots, page_tokens=16, n_pages=n_pages, max_new_tokens=wl.cap,
-                          eos_id=m.eos_id, max_staleness=stale, mode=mode)
-        o.submit([np.zeros(wl.prompt_len, np.int32)] * wl.n_prompts, L)
-        return o
+        cfg = R.make_cfg(m, max_slots=wl.max_slots, max_prompt_len=wl.prompt_len, max_new_tokens=wl.cap,
+                         max_seqs=wl.n_prompts, kv_pool_bytes=wl.kv_pool_bytes, max_staleness=stale, mode=mode,
+                         debug_flags=R.ROLLOUT_DEBUG_NO_MODEL)
+        c = R.rollout_init(np.zeros(1, np.uint16), cfg)
+        R.rollout_submit(c, toks, offs, L.astype(np.uint32))
+        return c
 
-    o = mk()
-    ctx_sum = []
-    while o.queue or any(x is not None for x in o.slots):
-        o.step()
-        if len(o.finished) >= wl.harvest:
-            o.harvest(wl.harvest)
-        if o.queue:
-            ctx_sum.append(sum(len(s.prompt) + s.gen_len for s in o.slots if s is not None))
-    full = dict(steps=o.step_no, bubble=o.bubble_ratio(), n_stale=o.n_stale, n_preempt=o.n_preempt,
-                prefill_tokens=o.prefill_tokens, gen_tokens=o.gen_tokens)
-    sync = mk(mode=2, stale=-1)
-    sync.run_to_completion(wl.harvest)
-    full["bubble_sync_baseline"] = sync.bubble_ratio()
+    def run(c, until=None):
+        ctx_sum = []
+        while True:
+            i = R.rollout_step(c)
+            if i.n_finished_unharvested >= wl.harvest:
+                R.rollout_harvest(c, wl.harvest, 0, want_logp=False)
+            if i.n_queued:
+                ctx_sum.append(int(i.ctx_tokens))
+            if (until is not None and i.step >= until) or (i.n_active == 0 and i.n_queued == 0):
+                return ctx_sum
+
+    c = mk()
+    ctx_sum = run(c)
+    st = R.rollout_stats(c)
+    R.rollout_destroy(c)
+    full = dict(steps=int(st.steps), bubble=st.idle / (wl.max_slots * st.steps), n_stale=int(st.n_stale),
+                n_preempt=int(st.n_preempt), prefill_tokens=int(st.prefill_tokens), gen_tokens=int(st.gen_tokens))
+    c = mk(mode=2, stale=-1)
+    run(c)
+    st = R.rollout_stats(c)
+    R.rollout_destroy(c)
+    full["bubble_sync_baseline"] = st.idle / (wl.max_slots * st.steps)
     target = float(np.mean(ctx_sum))
     s0 = int(np.argmin(np.abs(np.array(ctx_sum) - target)))
-    o = mk()
-    while o.step_no <= s0:
-        o.step()
-        if len(o.finished) >= wl.harvest:
-            o.harvest(wl.harvest)
-    running = [(s.seq_id, s.gen_len) for s in o.slots if s is not None]
-    queued = [(s.seq_id, s.gen_len) for s in o.queue]
-    return dict(step=s0, running=running, queued=queued, mean_ctx_sum=target), full
+    c = mk()
+    run(c, until=s0)
+    running, queued = [], []
+    for sid in range(wl.n_prompts):
+        tk, _, state, slot = R.rollout_peek(c, sid, wl.cap)
+        if state == 1:
+            running.append((slot, sid, len(tk)))
+        elif state == 0:
+            queued.append((0 if len(tk) else 1, sid, len(tk)))   # resumed rollouts wait ahead of fresh prompts
+    R.rollout_destroy(c)
+    return dict(step=s0, running=[(sid, g) for _, sid, g in sorted(running)],
+                queued=[(sid, g) for _, sid, g in sorted(queued)], mean_ctx_sum=target), full
 
 
 def cpu_baseline(wl, ctx_lens, budget_s=20.0):
@@ -271,8 +286,8 @@ def main():
     if args.full_run:
         return full_run(torch, R, W, wl, m, L)
     t0 = time.time()
-    snap, full = scheduler_snapshot(wl, L)
-    print(f"[bench] scheduler oracle: {full} snapshot step {snap['step']} ({time.time() - t0:.1f}s)", file=sys.stderr)
+    snap, full = scheduler_snapshot(R, wl, L)
+    print(f"[bench] scheduler-only pass: {full} snapshot step {snap['step']} ({time.time() - t0:.1f}s)", file=sys.stderr)
 
     attn = None if args.no_attn_alone else attention_alone(torch, R)
     if attn:

@@ -86,6 +86,8 @@ typedef struct rollout_step_info {
   uint32_t n_admitted;             /* admitted (prefilled) this step */
   uint32_t n_finished_step;
   uint32_t n_preempted_step;
+  uint64_t ctx_tokens;             /* cached tokens over the running requests after the step: what the next step's
+                                      decode attention reads (times the per-token KV bytes) */
 } rollout_step_info;
 
 typedef struct rollout_traj {

@@ -65,7 +65,7 @@ class rollout_cfg(C.Structure):
 class rollout_step_info(C.Structure):
     _fields_ = [("step", C.c_uint64)] + [(n, C.c_uint32) for n in
                 ("n_ran", "n_active", "n_finished_unharvested", "n_queued", "free_pages", "n_admitted",
-                 "n_finished_step", "n_preempted_step")]
+                 "n_finished_step", "n_preempted_step")] + [("ctx_tokens", C.c_uint64)]
 
 
 class rollout_traj(C.Structure):

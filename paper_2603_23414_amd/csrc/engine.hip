@@ -414,6 +414,7 @@ int step_impl(rollout_ctx* c, const int32_t* forced_tok, float* logits_out, roll
     info->n_admitted = (uint32_t)sh[STAT_NADM];
     info->n_finished_step = (uint32_t)sh[STAT_NFIN_STEP];
     info->n_preempted_step = (uint32_t)sh[STAT_NPRE_STEP];
+    info->ctx_tokens = (uint64_t)(unsigned)sh[STAT_CTX_LO] | ((uint64_t)(unsigned)sh[STAT_CTX_HI] << 32);
   }
   c->wall_ms_steps += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
   (void)logits_out;
@@ -497,8 +498,10 @@ int rollout_init(rollout_ctx** out, const void* weights, size_t weights_bytes, c
   if (n_pages > (1ll << 30)) n_pages = 1ll << 30;
   c->n_pages = (int)n_pages;
   c->layer_pool_bytes = (size_t)c->n_pages * page_layer_bytes;
-  INIT_TRY(dev_alloc(c, &c->kv_pool, c->layer_pool_bytes * c->NL));
-  INIT_HIP(hipMemsetAsync(c->kv_pool, 0, c->layer_pool_bytes * c->NL, c->stream));
+  if (!(f.debug_flags & ROLLOUT_DEBUG_NO_MODEL)) {   // a scheduler-only context counts pages but never touches them
+    INIT_TRY(dev_alloc(c, &c->kv_pool, c->layer_pool_bytes * c->NL));
+    INIT_HIP(hipMemsetAsync(c->kv_pool, 0, c->layer_pool_bytes * c->NL, c->stream));
+  }
 
   // ---- RoPE table: cos/sin of pos * theta^(-2i/d), evaluated in double --------------------------------
   {
