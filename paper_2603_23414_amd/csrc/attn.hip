@@ -1,15 +1,19 @@
 // Ragged paged GQA decode attention for gfx950 (the KV-streaming half of the rollout step; the paper,
 // Sec. 2.2, names KV-cache loading as what bounds autoregressive rollout).
 //
-// One wavefront owns one work item = (row, kv head, chunk of cached tokens; the chunk size is picked per launch).  A row is one
-// query token of one slot; all G query heads that share the kv head are computed from a single pass
-// over the K/V bytes.  The page layout makes both phases stream 16-byte vectors that are contiguous
+// One wavefront owns (row, kv head, chunk of cached tokens; the chunk size is picked per launch); the four wavefronts
+// of a workgroup take four consecutive chunks of the same (row, kv head) and merge their results through LDS, so a
+// row of up to four chunks leaves the kernel finished and a longer one writes one partial result per four chunks
+// (those stores are what the kernel pays most for after the K/V stream itself: about 3 us per MB of partials,
+// measured by removing them).  A row is one query token of one slot; all G query heads that share the kv head are
+// computed from a single pass over the K/V bytes.  The page layout makes both phases stream 16-byte vectors that are contiguous
 // across lanes with no LDS staging of K or V:
 //   K block [d/8][16 tokens][8 dims]  -> score phase, one lane per token (16 lanes cover one page)
 //   V block [2][d][8 tokens]          -> value phase, one lane per output dim, tokens paired for dot2
 // Scores and values use v_dot2c_f32_bf16 with the query held in scalar registers; probabilities go
 // through a 512-byte per-wave LDS tile (bf16) to be re-read as broadcast operands.  Softmax statistics
-// and accumulators are fp32.  Chunks of one row are merged by k_attn_merge (log-sum-exp merge).
+// and accumulators are fp32.  Chunk groups of one row are merged by k_attn_merge (log-sum-exp merge).
+#define ATTN_GROUP ATTN_GROUP_CHUNKS   // chunks per workgroup
 #include "common.h"
 #include "kernels.h"
 
@@ -19,24 +23,28 @@ template <int D, int G>
 __global__ __launch_bounds__(256) void k_decode_attn(
     const uint8_t* __restrict__ pool, const uint16_t* __restrict__ q, const int* __restrict__ row_slot,
     const int* __restrict__ row_pos, const int* __restrict__ page_table, int max_pages,
-    const int2* __restrict__ work, int Hkv, float* __restrict__ part_acc, float* __restrict__ part_ml,
+    const int4* __restrict__ work, int Hkv, float* __restrict__ part_acc, float* __restrict__ part_ml,
     void* __restrict__ out, int out_fp32, float scale_log2e, int chunk_tokens) {
   constexpr int NCH = D / 8;
   constexpr int DPL = (D + 63) / 64;
   constexpr int KBYTES = PAGE_TOKENS * D * 2;
   constexpr int BLK = 2 * KBYTES;
-  __shared__ __align__(16) uint16_t p_lds[4][G][64];
+  __shared__ __align__(16) uint16_t p_lds[ATTN_GROUP][G][64];
+  __shared__ float acc_s[ATTN_GROUP][G][DPL * 64];
+  __shared__ float ml_s[ATTN_GROUP][G][2];
 
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: keeps q addressing scalar
-  const int kvh = blockIdx.y * 4 + w;
-  if (kvh >= Hkv) return;                       // whole wave leaves; no block-wide barrier below
-  const int2 it = work[blockIdx.x];
-  const int row = it.x, chunk = it.y;
-  const int slot = row_slot[row];
-  const int ctx = row_pos[row] + 1;
-  const int tok0 = chunk * chunk_tokens;
-  const int tok_end = min(ctx, tok0 + chunk_tokens);
+  const int kvh = blockIdx.y;
+  const int4 it = work[blockIdx.x];               // one load, then page ids and query go out together
+  const int row = it.x, group = it.y, slot = it.z, ctx = it.w;
+  // the group's token range is cut evenly (in 64-token tiles) over the four wavefronts, so they finish together; a
+  // wavefront left without tokens contributes weight zero to the merge
+  const int r0 = group * (ATTN_GROUP * chunk_tokens);
+  const int r1 = min(ctx, r0 + ATTN_GROUP * chunk_tokens);
+  const int span = (r1 - r0 + ATTN_GROUP * 64 - 1) / (ATTN_GROUP * 64) * 64;   // <= chunk_tokens
+  const int tok0 = r0 + w * span;
+  const int tok_end = min(r1, tok0 + span);
   const int last_page = (ctx - 1) >> 4;
   const int* __restrict__ pt = page_table + (size_t)slot * max_pages;
   const int Hq = Hkv * G;
@@ -51,8 +59,8 @@ __global__ __launch_bounds__(256) void k_decode_attn(
     for (int dd = 0; dd < DPL; ++dd) acc[h][dd] = 0.f;
   }
 
-  // page ids of the whole chunk (at most 64 pages), fetched once: lane i holds logical page chunk*ppc + i
-  const int pgs = pt[min(chunk * (chunk_tokens / PAGE_TOKENS) + lane, last_page)];
+  // page ids of this wavefront's span (at most 64 pages), fetched once: lane i holds logical page tok0/16 + i
+  const int pgs = pt[min((tok0 >> 4) + lane, last_page)];
 
   for (int t0 = tok0; t0 < tok_end; t0 += 64) {
     const int tile = (t0 - tok0) >> 6;
@@ -142,20 +150,44 @@ __global__ __launch_bounds__(256) void k_decode_attn(
     }
   }
 
-  const int nchunks = (ctx + chunk_tokens - 1) / chunk_tokens;
+  // ---- merge the workgroup's chunks through LDS (fixed order: the result does not depend on scheduling) -------
 #pragma unroll
   for (int h = 0; h < G; ++h) {
     const float lsum = wave_sum(l[h]);
+#pragma unroll
+    for (int dd = 0; dd < DPL; ++dd) acc_s[w][h][lane + dd * 64] = acc[h][dd];
+    if (lane == 0) {
+      ml_s[w][h][0] = m[h];
+      ml_s[w][h][1] = lsum;
+    }
+  }
+  __syncthreads();
+  const int nchunks = (ctx + chunk_tokens - 1) / chunk_tokens;
+  const int ngroups = (nchunks + ATTN_GROUP - 1) / ATTN_GROUP;
+  for (int h = w; h < G; h += ATTN_GROUP) {       // wave w finishes heads w, w + 4, ..
+    float mx = NEG_BIG;
+#pragma unroll
+    for (int u = 0; u < ATTN_GROUP; ++u) mx = fmaxf(mx, ml_s[u][h][0]);
+    float den = 0.f, num[DPL];
+#pragma unroll
+    for (int dd = 0; dd < DPL; ++dd) num[dd] = 0.f;
+#pragma unroll
+    for (int u = 0; u < ATTN_GROUP; ++u) {
+      const float wgt = __builtin_amdgcn_exp2f(ml_s[u][h][0] - mx);
+      den += wgt * ml_s[u][h][1];
+#pragma unroll
+      for (int dd = 0; dd < DPL; ++dd) num[dd] += wgt * acc_s[u][h][lane + dd * 64];
+    }
     const int head = kvh * G + h;
-    if (nchunks == 1) {
-      const float inv = 1.f / lsum;
+    if (ngroups == 1) {
+      const float inv = 1.f / den;
 #pragma unroll
       for (int dd = 0; dd < DPL; ++dd) {
         const int dim = lane + dd * 64;
         if (D >= 64 || dim < D) {
           const size_t o = ((size_t)row * Hq + head) * D + dim;
-          if (out_fp32) ((float*)out)[o] = acc[h][dd] * inv;
-          else ((uint16_t*)out)[o] = f2bf(acc[h][dd] * inv);
+          if (out_fp32) ((float*)out)[o] = num[dd] * inv;
+          else ((uint16_t*)out)[o] = f2bf(num[dd] * inv);
         }
       }
     } else {
@@ -163,24 +195,24 @@ __global__ __launch_bounds__(256) void k_decode_attn(
 #pragma unroll
       for (int dd = 0; dd < DPL; ++dd) {
         const int dim = lane + dd * 64;
-        if (D >= 64 || dim < D) part_acc[pi * D + dim] = acc[h][dd];
+        if (D >= 64 || dim < D) part_acc[pi * D + dim] = num[dd];
       }
       if (lane == 0) {
-        part_ml[pi * 2] = m[h];
-        part_ml[pi * 2 + 1] = lsum;
+        part_ml[pi * 2] = mx;
+        part_ml[pi * 2 + 1] = den;
       }
     }
   }
 }
 
-// Merge the chunk partials of one (row, query head): out = sum_c 2^(m_c - m*) acc_c / sum_c 2^(m_c - m*) l_c.
+// Merge the chunk-group partials of one (row, query head): out = sum_c 2^(m_c - m*) acc_c / sum_c 2^(m_c - m*) l_c.
 template <int D>
 __global__ void k_attn_merge(const int* __restrict__ row_pos, const int* __restrict__ row_wstart, int Hq,
                              const float* __restrict__ part_acc, const float* __restrict__ part_ml,
                              void* __restrict__ out, int out_fp32, int chunk_tokens) {
   const int row = blockIdx.x, head = blockIdx.y, dim = threadIdx.x;
   const int ctx = row_pos[row] + 1;
-  const int n = (ctx + chunk_tokens - 1) / chunk_tokens;
+  const int n = ((ctx + chunk_tokens - 1) / chunk_tokens + ATTN_GROUP - 1) / ATTN_GROUP;
   if (n == 1) return;
   const int ws = row_wstart[row];
   float mx = NEG_BIG;
@@ -215,8 +247,9 @@ __global__ void k_attn_merge(const int* __restrict__ row_pos, const int* __restr
 }
 
 // Build the (row, chunk) work list for n_rows rows on the device: one block, any n_rows.
-__global__ __launch_bounds__(1024) void k_attn_worklist(const int* __restrict__ row_pos, int n_rows,
-                                                        int2* __restrict__ work, int* __restrict__ row_wstart,
+__global__ __launch_bounds__(1024) void k_attn_worklist(const int* __restrict__ row_slot,
+                                                        const int* __restrict__ row_pos, int n_rows,
+                                                        int4* __restrict__ work, int* __restrict__ row_wstart,
                                                         int* __restrict__ n_work_out, int chunk_tokens) {
   __shared__ int scan[1024];
   __shared__ int base;
@@ -224,7 +257,7 @@ __global__ __launch_bounds__(1024) void k_attn_worklist(const int* __restrict__ 
   __syncthreads();
   for (int r0 = 0; r0 < n_rows; r0 += 1024) {
     const int r = r0 + threadIdx.x;
-    const int nch = r < n_rows ? (row_pos[r] + 1 + chunk_tokens - 1) / chunk_tokens : 0;
+    const int nch = r < n_rows ? ((row_pos[r] + 1 + chunk_tokens - 1) / chunk_tokens + ATTN_GROUP - 1) / ATTN_GROUP : 0;
     scan[threadIdx.x] = nch;
     __syncthreads();
     for (int o = 1; o < 1024; o <<= 1) {
@@ -236,7 +269,7 @@ __global__ __launch_bounds__(1024) void k_attn_worklist(const int* __restrict__ 
     const int start = base + scan[threadIdx.x] - nch;
     if (r < n_rows) {
       row_wstart[r] = start;
-      for (int c = 0; c < nch; ++c) work[start + c] = make_int2(r, c);
+      for (int c = 0; c < nch; ++c) work[start + c] = make_int4(r, c, row_slot[r], row_pos[r] + 1);
     }
     __syncthreads();
     if (threadIdx.x == 1023) base += scan[1023];
@@ -270,16 +303,16 @@ int attn_supported(int head_dim, int group) {
   return (head_dim == 128 && (group == 1 || group == 4 || group == 5)) || (head_dim == 32 && (group == 1 || group == 4));
 }
 
-void launch_attn_worklist(const int* row_pos, int n_rows, int2* work, int* row_wstart, int* n_work_out,
+void launch_attn_worklist(const int* row_slot, const int* row_pos, int n_rows, int4* work, int* row_wstart, int* n_work_out,
                           int chunk_tokens, hipStream_t st) {
-  hipLaunchKernelGGL(k_attn_worklist, dim3(1), dim3(1024), 0, st, row_pos, n_rows, work, row_wstart, n_work_out,
+  hipLaunchKernelGGL(k_attn_worklist, dim3(1), dim3(1024), 0, st, row_slot, row_pos, n_rows, work, row_wstart, n_work_out,
                      chunk_tokens);
 }
 
 template <int D, int G>
 static void launch_attn_t(const AttnArgs& a, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   const float scale = 1.4426950408889634f / sqrtf((float)D);
-  dim3 grid(a.n_work, (a.Hkv + 3) / 4);
+  dim3 grid(a.n_work, a.Hkv);
   if (ev0) (void)hipEventRecord(ev0, st);
   hipLaunchKernelGGL((k_decode_attn<D, G>), grid, dim3(256), 0, st, (const uint8_t*)a.pool, (const uint16_t*)a.q,
                      a.row_slot, a.row_pos, a.page_table, a.max_pages, a.work, a.Hkv, a.part_acc, a.part_ml, a.out,

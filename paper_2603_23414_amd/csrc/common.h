@@ -4,17 +4,25 @@
 #include <stdint.h>
 
 #define PAGE_TOKENS 16
-// A decode-attention work item covers `chunk` cached tokens of one (row, kv head); the chunk is chosen per launch:
-// a multiple of 64 between ATTN_CHUNK_MIN and ATTN_CHUNK_MAX, about (sum of contexts) * n_kv_heads / ATTN_TARGET_ITEMS,
-// i.e. roughly two rounds of work items over the chip's resident wavefronts: large chunks when the batch is full
-// (fewer partial results to merge), small chunks when a few long rollouts are left (tail drain) so they still spread.
+// A decode-attention wavefront covers `chunk` cached tokens of one (row, kv head), a workgroup ATTN_GROUP_CHUNKS
+// consecutive chunks (one work item of the list); the chunk is chosen per launch: a multiple of 64 between
+// ATTN_CHUNK_MIN and ATTN_CHUNK_MAX, about (sum of contexts) * n_kv_heads / ATTN_TARGET_ITEMS, i.e. roughly five
+// rounds of wavefronts over the chip's resident ones (measured: 481 us at two rounds, 469 at three, 465 at four, 461
+// at five to eight, slower again below 256 tokens per wavefront):
+// fine enough that the end of the launch stays busy, and small in the tail drain so that a few long rollouts still
+// spread over the chip.
+#define ATTN_GROUP_CHUNKS 4
 #define ATTN_CHUNK_MIN 256
 #define ATTN_CHUNK_MAX 1024         // 64 pages: their ids fit one register across a wavefront
-#define ATTN_TARGET_ITEMS 6144      // 256 CUs x 4 SIMDs x 3 resident waves x 2 rounds
+#define ATTN_TARGET_ITEMS 16384     // 256 CUs x 4 SIMDs x 3 resident waves x 5.3 rounds
 __host__ __device__ __forceinline__ int attn_pick_chunk(unsigned long long total_ctx, int n_kv_heads) {
   unsigned long long c = (total_ctx * (unsigned long long)n_kv_heads + ATTN_TARGET_ITEMS - 1) / ATTN_TARGET_ITEMS;
   c = (c + 63) / 64 * 64;
   return c < ATTN_CHUNK_MIN ? ATTN_CHUNK_MIN : c > ATTN_CHUNK_MAX ? ATTN_CHUNK_MAX : (int)c;
+}
+// work items (workgroups per kv head) of a row with `ctx` cached tokens
+__host__ __device__ __forceinline__ int attn_row_items(int ctx, int chunk) {
+  return ((ctx + chunk - 1) / chunk + ATTN_GROUP_CHUNKS - 1) / ATTN_GROUP_CHUNKS;
 }
 #define WAVE 64
 

@@ -271,7 +271,7 @@ int fill_weights(rollout_ctx* c, const void* weights, size_t weights_bytes) {
 }
 
 // ---- the per-step kernel chain over a set of rows (decode rows or one prefill pass) ---------------------
-void run_layers(rollout_ctx* c, int R, const int* row_slot, const int* row_pos, const int* row_tok, const int2* work,
+void run_layers(rollout_ctx* c, int R, const int* row_slot, const int* row_pos, const int* row_tok, const int4* work,
                 const int* row_wstart, int n_work, int chunk_tokens, bool time_attn, const PfTileHost* pf_tiles = nullptr,
                 int n_tiles = 0) {
   hipStream_t st = c->stream;
@@ -909,7 +909,7 @@ static AttnWs attn_ws_layout(uint32_t n, uint64_t max_work, uint32_t Hq, uint32_
   w.row_slot = o; o = align256(o + 4ull * n);
   w.row_pos = o; o = align256(o + 4ull * n);
   w.row_wstart = o; o = align256(o + 4ull * n);
-  w.work = o; o = align256(o + 8ull * max_work);
+  w.work = o; o = align256(o + 16ull * max_work);
   w.part_ml = o; o = align256(o + 8ull * max_work * Hq);
   w.part_acc = o; o = align256(o + 4ull * max_work * Hq * d);
   w.total = o;
@@ -934,20 +934,20 @@ int rollout_attn_plan(const int32_t* ctx_len, uint32_t n, uint32_t n_q_heads, ui
   const AttnWs w = attn_ws_layout(n, max_work, n_q_heads, head_dim);
   if (w.total > workspace_bytes) return fail(nullptr, ROLLOUT_EINVAL, "workspace too small");
   std::vector<int> rs(n), rp(n), ws(n);
-  std::vector<int2> work;
+  std::vector<int4> work;
   work.reserve(max_work);
   for (uint32_t i = 0; i < n; ++i) {
     rs[i] = (int)i;
     rp[i] = ctx_len[i] - 1;
     ws[i] = (int)work.size();
-    const int nch = (ctx_len[i] + chunk - 1) / chunk;
-    for (int ch = 0; ch < nch; ++ch) work.push_back(make_int2((int)i, ch));
+    const int nch = attn_row_items(ctx_len[i], chunk);
+    for (int ch = 0; ch < nch; ++ch) work.push_back(make_int4((int)i, ch, (int)i, ctx_len[i]));
   }
   uint8_t* base = (uint8_t*)workspace_dev;
   if (hipMemcpy(base + w.row_slot, rs.data(), 4ull * n, hipMemcpyHostToDevice) != hipSuccess ||
       hipMemcpy(base + w.row_pos, rp.data(), 4ull * n, hipMemcpyHostToDevice) != hipSuccess ||
       hipMemcpy(base + w.row_wstart, ws.data(), 4ull * n, hipMemcpyHostToDevice) != hipSuccess ||
-      hipMemcpy(base + w.work, work.data(), 8ull * work.size(), hipMemcpyHostToDevice) != hipSuccess)
+      hipMemcpy(base + w.work, work.data(), 16ull * work.size(), hipMemcpyHostToDevice) != hipSuccess)
     return fail(nullptr, ROLLOUT_EDEVICE, "hipMemcpy failed");
   *n_work = (uint32_t)work.size();
   *chunk_tokens = (uint32_t)chunk;
@@ -974,7 +974,7 @@ int rollout_attn_decode(const void* pool_dev, uint32_t n_q_heads, uint32_t n_kv_
   a.row_pos = (const int*)(base + w.row_pos);
   a.page_table = page_table_dev;
   a.max_pages = (int)max_pages;
-  a.work = (const int2*)(base + w.work);
+  a.work = (const int4*)(base + w.work);
   a.row_wstart = (const int*)(base + w.row_wstart);
   a.n_work = (int)n_work;
   a.n_rows = (int)n;

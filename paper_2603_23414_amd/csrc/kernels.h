@@ -12,7 +12,7 @@ struct AttnArgs {
   const int* row_pos;      // position of the query token (context = pos + 1)
   const int* page_table;   // int32 [slots][max_pages]
   int max_pages;
-  const int2* work;        // (row, chunk) items
+  const int4* work;        // (row, chunk, page-table row, context length) items: all a wavefront needs to start
   const int* row_wstart;   // first work item of each row
   int n_work, n_rows, Hkv;
   float* part_acc;         // [n_work][Hq][d]
@@ -23,7 +23,7 @@ struct AttnArgs {
   int chunk_tokens;        // cached tokens per work item (multiple of 64, at most 1024)
 };
 int attn_supported(int head_dim, int group);
-void launch_attn_worklist(const int* row_pos, int n_rows, int2* work, int* row_wstart, int* n_work_out,
+void launch_attn_worklist(const int* row_slot, const int* row_pos, int n_rows, int4* work, int* row_wstart, int* n_work_out,
                           int chunk_tokens, hipStream_t st);
 void launch_decode_attn(const AttnArgs& a, int head_dim, int group, hipStream_t st, hipEvent_t ev0 = nullptr,
                         hipEvent_t ev1 = nullptr);
@@ -90,7 +90,7 @@ struct SchedDev {
   int max_shared;
   int *q_ring, *free_stack, *fin_list;
   int *row_slot, *row_pos, *row_tok, *row_wstart;
-  int2* work;
+  int4* work;
   const int* row_argmax;
   const float* row_lse;
   const float* logits;

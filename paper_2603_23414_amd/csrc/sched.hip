@@ -56,7 +56,7 @@ __device__ void rebuild_rows_and_status(const SchedDev& d, int* sh, int r_this_s
   block_scan_excl(sidx >= 0 ? ((pos + 1) >> 16) : 0, &hi_tot, sh);
   const unsigned long long ctx_total = (unsigned long long)lo_tot + ((unsigned long long)hi_tot << 16);
   const int chunk = attn_pick_chunk(ctx_total, d.Hkv);
-  const int nch = sidx >= 0 ? (pos + 1 + chunk - 1) / chunk : 0;
+  const int nch = sidx >= 0 ? attn_row_items(pos + 1, chunk) : 0;
   int n_active, n_work;
   const int rank = block_scan_excl(sidx >= 0 ? 1 : 0, &n_active, sh);
   const int wstart = block_scan_excl(nch, &n_work, sh);
@@ -65,7 +65,7 @@ __device__ void rebuild_rows_and_status(const SchedDev& d, int* sh, int r_this_s
     d.row_pos[rank] = pos;
     d.row_tok[rank] = d.seq_tokens[(size_t)sidx * d.tok_stride + pos];
     d.row_wstart[rank] = wstart;
-    for (int c = 0; c < nch; ++c) d.work[wstart + c] = make_int2(rank, c);
+    for (int c = 0; c < nch; ++c) d.work[wstart + c] = make_int4(rank, c, t, pos + 1);
   }
   if (t == 0) {
     d.sc[SC_NDEC] = n_active;

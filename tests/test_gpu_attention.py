@@ -29,7 +29,8 @@ def _run_case(lens, Hq, Hkv, d, seed, out_fp32=True, poison=True):
     ws_bytes = R.rollout_attn_workspace_bytes(n, int(lens.sum()), Hq, d)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     n_work, chunk = R.rollout_attn_plan(lens, Hq, Hkv, d, ws.data_ptr(), ws_bytes)
-    assert chunk % 64 == 0 and 256 <= chunk <= 1024 and n_work == int(((lens + chunk - 1) // chunk).sum())
+    # one work item (workgroup per kv head) per four consecutive chunks of a row
+    assert chunk % 64 == 0 and 256 <= chunk <= 1024 and n_work == int(((((lens + chunk - 1) // chunk) + 3) // 4).sum())
     q_d = t(q.view(np.int16))
     out = torch.full((n, Hq, d), float("nan"), dtype=torch.float32 if out_fp32 else torch.bfloat16, device=dev)
     R.rollout_attn_decode(pool.data_ptr(), Hq, Hkv, d, q_d.data_ptr(), tab_d.data_ptr(), table.shape[1], n, n_work,
