@@ -313,7 +313,7 @@ int gemm_pick_splits(int M, int N, int K) {
   const int tiles = ((N + 127) / 128) * mblocks;
   const int nkb = K / GEMM_BK;
   int S = 1;
-  if (tiles < 192) S = (256 + tiles - 1) / tiles;
+  if (tiles < 192) S = M > 128 ? 256 / tiles : (256 + tiles - 1) / tiles;   // M > 128: stay within one workgroup per CU (deep kernel)
   if (S > 8) S = 8;
   if (S > nkb / 4) S = nkb / 4 > 0 ? nkb / 4 : 1;
   const int per = (nkb + S - 1) / S;
