@@ -315,8 +315,17 @@ def main():
     offs[1:] = np.cumsum([len(p) for p in prompts])
     R.rollout_submit(ctx, np.concatenate(prompts), offs, targets)
 
+    # algorithmic HBM bytes of one step (what the method must move): every weight once, the cached K/V of every running
+    # rollout, the new K/V rows and the fp32 logits rows
+    weight_bytes = 2 * (W.weight_count(m) - m.vocab * m.d_model)      # the embedding table is gathered, not streamed
+    kv_bytes_per_tok = m.n_layers * m.n_kv_heads * 2 * m.head_dim * 2
+    model_bytes = [0]
+    ctx_before = [0]
+
     def one_step():
         i = R.rollout_step(ctx)
+        model_bytes[0] += weight_bytes + (ctx_before[0] + i.n_ran) * kv_bytes_per_tok + i.n_ran * m.vocab * 4
+        ctx_before[0] = int(i.ctx_tokens)
         if i.n_finished_unharvested >= wl.harvest:
             R.rollout_harvest(ctx, wl.harvest, 0, want_logp=True)
         return i
@@ -330,6 +339,7 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     tokens = 0
+    model_bytes[0] = 0
     for _ in range(args.steps):
         tokens += one_step().n_ran
     torch.cuda.synchronize()
@@ -366,6 +376,10 @@ def main():
                bubble_ratio=dict(whole_run_steps=full["bubble"], sync_baseline_steps=full["bubble_sync_baseline"],
                                  window=(s1.idle - s0.idle) / max(1, wl.max_slots * (s1.steps - s0.steps)),
                                  whole_run_n_steps=full["steps"], n_stale=full["n_stale"], n_preempt=full["n_preempt"]),
+               end_to_end_hbm=dict(alg_bytes_per_step=model_bytes[0] / args.steps, achieved=model_bytes[0] / dt / 1e9,
+                                   peak=8000.0, unit="GB/s", frac=model_bytes[0] / dt / 1e9 / 8000.0,
+                                   note="weights once + cached K/V of every running rollout + new K/V + fp32 logits, "
+                                        "per step, over the wall time of the timed steps (prefill flops not counted)"),
                attn_alone=attn)
     if not args.no_cpu_baseline:
         live = [wl.prompt_len + gl for _, gl in snap["running"]]
