@@ -21,8 +21,7 @@
 
 template <int D, int G>
 __global__ __launch_bounds__(256) void k_decode_attn(
-    const uint8_t* __restrict__ pool, const uint16_t* __restrict__ q, const int* __restrict__ row_slot,
-    const int* __restrict__ row_pos, const int* __restrict__ page_table, int max_pages,
+    const uint8_t* __restrict__ pool, const uint16_t* __restrict__ q, const int* __restrict__ page_table, int max_pages,
     const int4* __restrict__ work, int Hkv, float* __restrict__ part_acc, float* __restrict__ part_ml,
     void* __restrict__ out, int out_fp32, float scale_log2e, int chunk_tokens) {
   constexpr int NCH = D / 8;
@@ -315,7 +314,7 @@ static void launch_attn_t(const AttnArgs& a, hipStream_t st, hipEvent_t ev0, hip
   dim3 grid(a.n_work, a.Hkv);
   if (ev0) (void)hipEventRecord(ev0, st);
   hipLaunchKernelGGL((k_decode_attn<D, G>), grid, dim3(256), 0, st, (const uint8_t*)a.pool, (const uint16_t*)a.q,
-                     a.row_slot, a.row_pos, a.page_table, a.max_pages, a.work, a.Hkv, a.part_acc, a.part_ml, a.out,
+                     a.page_table, a.max_pages, a.work, a.Hkv, a.part_acc, a.part_ml, a.out,
                      a.out_fp32, scale, a.chunk_tokens);
   if (ev1) (void)hipEventRecord(ev1, st);
   if (a.need_merge)
