@@ -79,3 +79,14 @@ def test_long_tail_mix_like_the_benchmark_case():
     got, ref = _run_case(lens, 32, 8, 128, seed=12)
     assert np.isfinite(got).all()
     assert np.abs(got - ref).max() < TOL
+
+
+@pytest.mark.parametrize("Hq,Hkv,d", [(32, 8, 128), (40, 8, 128), (8, 2, 32)])
+def test_group_boundaries_of_the_workgroup_merge(Hq, Hkv, d):
+    """A workgroup merges four token spans in LDS and rows longer than four chunks go through the partial merge:
+    contexts just below, at and above one, four, five and eight chunks of the smallest chunk size (256), whose
+    last spans hold anything from a single token to a full tile."""
+    lens = [255, 256, 257, 1023, 1024, 1025, 1087, 1088, 1089, 1281, 2047, 2048, 2049, 4095, 4096, 4097, 5000]
+    got, ref = _run_case(lens, Hq, Hkv, d, seed=20 + Hq)
+    assert np.isfinite(got).all()
+    assert np.abs(got - ref).max(axis=(1, 2)).max() < TOL
