@@ -47,6 +47,7 @@ def _scheduler_only(L, *, Q, P, cap, G, kv_pool_pages=0, max_staleness=-1, mode=
             io = orc.step()
             ig = R.rollout_step(ctx)
             assert info_tuple(ig) == info_tuple(io), (info_tuple(ig), info_tuple(io))
+            assert ig.ctx_tokens == sum(len(s.prompt) + s.gen_len for s in orc.slots if s is not None)
             for slot in range(0, Q, max(1, Q // 4)):                  # sampled page tables
                 s = orc.slots[slot]
                 pages = R.rollout_slot_pages(ctx, slot, 4096)
