@@ -210,10 +210,11 @@ int rollout_attn_write_kv(void* pool_dev, uint32_t n_kv_heads, uint32_t head_dim
 /* Workspace bytes rollout_attn_plan / rollout_attn_decode need for n sequences whose lengths sum to total_ctx. */
 uint64_t rollout_attn_workspace_bytes(uint32_t n, uint64_t total_ctx, uint32_t n_q_heads, uint32_t head_dim);
 
-/* Build the (sequence, chunk) work list for context lengths ctx_len (host int32 [n], each >= 1) at the head of
- * workspace_dev.  The chunk (cached tokens per work item, a multiple of 64 in 256..1024) is chosen from the total
- * context so that the items make about two rounds over the chip; it is returned in chunk_tokens and must be
- * passed to rollout_attn_decode.  Synchronous (blocking host-to-device copies). */
+/* Build the work list for context lengths ctx_len (host int32 [n], each >= 1) at the head of workspace_dev: one item
+ * (one workgroup per kv head) per four consecutive chunks of a sequence.  The chunk (cached tokens per wavefront, a
+ * multiple of 64 in 128..1024) is chosen from the total context so that the wavefronts make about five rounds over
+ * the chip; it is returned in chunk_tokens and must be passed to rollout_attn_decode; n_work receives the number
+ * of items.  Synchronous (blocking host-to-device copies). */
 int rollout_attn_plan(const int32_t* ctx_len, uint32_t n, uint32_t n_q_heads, uint32_t n_kv_heads, uint32_t head_dim,
                       void* workspace_dev, uint64_t workspace_bytes, uint32_t* n_work, uint32_t* chunk_tokens);
 

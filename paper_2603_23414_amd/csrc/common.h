@@ -8,11 +8,11 @@
 // consecutive chunks (one work item of the list); the chunk is chosen per launch: a multiple of 64 between
 // ATTN_CHUNK_MIN and ATTN_CHUNK_MAX, about (sum of contexts) * n_kv_heads / ATTN_TARGET_ITEMS, i.e. roughly five
 // rounds of wavefronts over the chip's resident ones (measured: 481 us at two rounds, 469 at three, 465 at four, 461
-// at five to eight, slower again below 256 tokens per wavefront):
+// at five to eight; with little context in flight the floor of 128 tokens beats 256 by 5 % and 64 loses again):
 // fine enough that the end of the launch stays busy, and small in the tail drain so that a few long rollouts still
 // spread over the chip.
 #define ATTN_GROUP_CHUNKS 4
-#define ATTN_CHUNK_MIN 256
+#define ATTN_CHUNK_MIN 128
 #define ATTN_CHUNK_MAX 1024         // 64 pages: their ids fit one register across a wavefront
 #define ATTN_TARGET_ITEMS 16384     // 256 CUs x 4 SIMDs x 3 resident waves x 5.3 rounds
 __host__ __device__ __forceinline__ int attn_pick_chunk(unsigned long long total_ctx, int n_kv_heads) {

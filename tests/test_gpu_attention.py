@@ -30,7 +30,7 @@ def _run_case(lens, Hq, Hkv, d, seed, out_fp32=True, poison=True):
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     n_work, chunk = R.rollout_attn_plan(lens, Hq, Hkv, d, ws.data_ptr(), ws_bytes)
     # one work item (workgroup per kv head) per four consecutive chunks of a row
-    assert chunk % 64 == 0 and 256 <= chunk <= 1024 and n_work == int(((((lens + chunk - 1) // chunk) + 3) // 4).sum())
+    assert chunk % 64 == 0 and 128 <= chunk <= 1024 and n_work == int(((((lens + chunk - 1) // chunk) + 3) // 4).sum())
     q_d = t(q.view(np.int16))
     out = torch.full((n, Hq, d), float("nan"), dtype=torch.float32 if out_fp32 else torch.bfloat16, device=dev)
     R.rollout_attn_decode(pool.data_ptr(), Hq, Hkv, d, q_d.data_ptr(), tab_d.data_ptr(), table.shape[1], n, n_work,
@@ -84,9 +84,9 @@ def test_long_tail_mix_like_the_benchmark_case():
 @pytest.mark.parametrize("Hq,Hkv,d", [(32, 8, 128), (40, 8, 128), (8, 2, 32)])
 def test_group_boundaries_of_the_workgroup_merge(Hq, Hkv, d):
     """A workgroup merges four token spans in LDS and rows longer than four chunks go through the partial merge:
-    contexts just below, at and above one, four, five and eight chunks of the smallest chunk size (256), whose
-    last spans hold anything from a single token to a full tile."""
-    lens = [255, 256, 257, 1023, 1024, 1025, 1087, 1088, 1089, 1281, 2047, 2048, 2049, 4095, 4096, 4097, 5000]
+    contexts just below, at and above one, four, five, eight and sixteen chunks of the smallest chunk size (128),
+    whose last spans hold anything from a single token to a full tile."""
+    lens = [127, 128, 129, 255, 256, 257, 511, 512, 513, 575, 576, 577, 641, 1023, 1024, 1025, 2047, 2048, 2049, 4097, 5000]
     got, ref = _run_case(lens, Hq, Hkv, d, seed=20 + Hq)
     assert np.isfinite(got).all()
     assert np.abs(got - ref).max(axis=(1, 2)).max() < TOL
