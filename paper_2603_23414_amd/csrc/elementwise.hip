@@ -70,52 +70,73 @@ __global__ __launch_bounds__(1024) void k_rope_kvwrite(const float* __restrict__
                                                       uint16_t* __restrict__ q_out, uint8_t* __restrict__ pool,
                                                       const int* __restrict__ page_table, int max_pages, int Hq, int Hkv,
                                                       int d) {
+  // one work item = four consecutive dims: (Hq + Hkv) * d/8 rotation items (dims i..i+3 paired with i+d/2..), then
+  // Hkv * d/4 value items; head_dim is a multiple of 8, so every load is a float4 and q / K stores are 8 bytes
   const int r = blockIdx.x;
   const int pos = row_pos[r];
   const int slot = row_slot[r];
   const int Nqkv = (Hq + 2 * Hkv) * d;
-  const int half = d / 2;
+  const int half = d / 2, hq4 = half / 4;
   const float* src = part + (size_t)r * Nqkv;
   const int pg = page_table[(size_t)slot * max_pages + (pos >> 4)];
   const int tk = pos & 15;
   const size_t kbytes = (size_t)PAGE_TOKENS * d * 2;
-  const int n_rot = (Hq + Hkv) * half;
-  for (int e = threadIdx.x; e < n_rot; e += 1024) {
-    const int head = e / half, i = e % half;
-    const int c1 = head * d + i, c2 = c1 + half;
-    float x1 = 0.f, x2 = 0.f;
-    for (int s = 0; s < S; ++s) {
-      x1 += src[(size_t)s * part_stride + c1];
-      x2 += src[(size_t)s * part_stride + c2];
-    }
-    if (bias) {
-      x1 += bias[c1];
-      x2 += bias[c2];
-    }
-    const float2 cs = cs_table[(size_t)pos * half + i];
-    const float y1 = x1 * cs.x - x2 * cs.y;
-    const float y2 = x2 * cs.x + x1 * cs.y;
-    if (head < Hq) {
-      uint16_t* qo = q_out + ((size_t)r * Hq + head) * d;
-      qo[i] = f2bf(y1);
-      qo[i + half] = f2bf(y2);
-    } else {
-      const int kvh = head - Hq;
-      uint16_t* blk = (uint16_t*)(pool + ((size_t)pg * Hkv + kvh) * 2 * kbytes);
-      const int d1 = i, d2 = i + half;
-      blk[((d1 >> 3) * 16 + tk) * 8 + (d1 & 7)] = f2bf(y1);
-      blk[((d2 >> 3) * 16 + tk) * 8 + (d2 & 7)] = f2bf(y2);
-    }
-  }
-  const int n_v = Hkv * d;
+  const int n_rot = (Hq + Hkv) * hq4;
+  const int n_v = Hkv * d / 4;
   const int voff = (Hq + Hkv) * d;
-  for (int e = threadIdx.x; e < n_v; e += 1024) {
-    const int kvh = e / d, dim = e % d;
-    float x = 0.f;
-    for (int s = 0; s < S; ++s) x += src[(size_t)s * part_stride + voff + e];
-    if (bias) x += bias[voff + e];
-    uint16_t* blk = (uint16_t*)(pool + ((size_t)pg * Hkv + kvh) * 2 * kbytes);
-    blk[kbytes / 2 + ((size_t)(tk >> 3) * d + dim) * 8 + (tk & 7)] = f2bf(x);
+  for (int e = threadIdx.x; e < n_rot + n_v; e += 1024) {
+    if (e < n_rot) {
+      const int head = e / hq4, i = (e % hq4) * 4;
+      const int c1 = head * d + i, c2 = c1 + half;
+      float4 x1 = make_float4(0.f, 0.f, 0.f, 0.f), x2 = x1;
+      for (int s = 0; s < S; ++s) {
+        const float4 a = *(const float4*)(src + (size_t)s * part_stride + c1);
+        const float4 b = *(const float4*)(src + (size_t)s * part_stride + c2);
+        x1.x += a.x; x1.y += a.y; x1.z += a.z; x1.w += a.w;
+        x2.x += b.x; x2.y += b.y; x2.z += b.z; x2.w += b.w;
+      }
+      if (bias) {
+        const float4 a = *(const float4*)(bias + c1), b = *(const float4*)(bias + c2);
+        x1.x += a.x; x1.y += a.y; x1.z += a.z; x1.w += a.w;
+        x2.x += b.x; x2.y += b.y; x2.z += b.z; x2.w += b.w;
+      }
+      const float4 cs01 = *(const float4*)(cs_table + (size_t)pos * half + i);        // (cos, sin) of dims i, i+1
+      const float4 cs23 = *(const float4*)(cs_table + (size_t)pos * half + i + 2);
+      uint2 y1, y2;
+      y1.x = pack_bf2(x1.x * cs01.x - x2.x * cs01.y, x1.y * cs01.z - x2.y * cs01.w);
+      y1.y = pack_bf2(x1.z * cs23.x - x2.z * cs23.y, x1.w * cs23.z - x2.w * cs23.w);
+      y2.x = pack_bf2(x2.x * cs01.x + x1.x * cs01.y, x2.y * cs01.z + x1.y * cs01.w);
+      y2.y = pack_bf2(x2.z * cs23.x + x1.z * cs23.y, x2.w * cs23.z + x1.w * cs23.w);
+      if (head < Hq) {
+        uint16_t* qo = q_out + ((size_t)r * Hq + head) * d;
+        *(uint2*)(qo + i) = y1;
+        *(uint2*)(qo + i + half) = y2;
+      } else {
+        const int kvh = head - Hq;
+        uint16_t* blk = (uint16_t*)(pool + ((size_t)pg * Hkv + kvh) * 2 * kbytes);
+        const int d1 = i, d2 = i + half;                      // four dims stay inside one group of 8
+        *(uint2*)(blk + ((d1 >> 3) * 16 + tk) * 8 + (d1 & 7)) = y1;
+        *(uint2*)(blk + ((d2 >> 3) * 16 + tk) * 8 + (d2 & 7)) = y2;
+      }
+    } else {
+      const int ev = (e - n_rot) * 4;
+      const int kvh = ev / d, dim = ev % d;
+      float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+      for (int s = 0; s < S; ++s) {
+        const float4 a = *(const float4*)(src + (size_t)s * part_stride + voff + ev);
+        x.x += a.x; x.y += a.y; x.z += a.z; x.w += a.w;
+      }
+      if (bias) {
+        const float4 a = *(const float4*)(bias + voff + ev);
+        x.x += a.x; x.y += a.y; x.z += a.z; x.w += a.w;
+      }
+      uint16_t* vb = (uint16_t*)(pool + ((size_t)pg * Hkv + kvh) * 2 * kbytes) + kbytes / 2 +
+                     ((size_t)(tk >> 3) * d + dim) * 8 + (tk & 7);
+      vb[0] = f2bf(x.x);
+      vb[8] = f2bf(x.y);
+      vb[16] = f2bf(x.z);
+      vb[24] = f2bf(x.w);
+    }
   }
 }
 
