@@ -389,18 +389,48 @@ __global__ __launch_bounds__(64) void k_prefill_attn(const uint8_t* __restrict__
   float m_run = NEG_BIG, l_run = 0.f;
 
   const int n_kt = (last_key >> 5) + 1;
+  // software pipeline: the K fragments and the page id of key tile kt+1 and the V fragments of tile kt are all in
+  // flight while tile kt's scores are computed (a wave per workgroup has nothing else to hide those latencies with)
+  int pg = pt[min(c >> 4, last_page)];
+  u32x4 kf_next[NDC];
+  {
+    const uint8_t* kb = pool + ((size_t)pg * Hkv + kvh) * BLK + (c & 15) * 16 + g * 256;
+#pragma unroll
+    for (int dc = 0; dc < NDC; ++dc) kf_next[dc] = *(const u32x4*)(kb + dc * 512);
+  }
   for (int kt = 0; kt < n_kt; ++kt) {
-    const int km = kt * 32 + c;
-    const int pg = pt[min(km >> 4, last_page)];
-    const uint8_t* kb = pool + ((size_t)pg * Hkv + kvh) * BLK + (km & 15) * 16 + g * 256;
+    u32x4 kf[NDC];
+#pragma unroll
+    for (int dc = 0; dc < NDC; ++dc) kf[dc] = kf_next[dc];
+    const int pg_cur = pg;
+    // V fragments of this tile (both pages; a page wholly past the tile's last query is skipped below, its loads are
+    // clamped to the last valid page so they stay inside the slot's pages)
+    u32x4 vw[2][NMT];
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) {
+      const int pgs = __builtin_amdgcn_readlane(pg_cur, s2 * 16);
+      const uint8_t* vb = pool + ((size_t)pgs * Hkv + kvh) * BLK + KBYTES + g * 8;
+#pragma unroll
+      for (int mt = 0; mt < NMT; ++mt) {
+        const int dim = mt * 32 + c;
+        const u32x2 lo = *(const u32x2*)(vb + (size_t)dim * 16);
+        const u32x2 hi = *(const u32x2*)(vb + (size_t)(D + dim) * 16);
+        vw[s2][mt].x = lo.x; vw[s2][mt].y = lo.y; vw[s2][mt].z = hi.x; vw[s2][mt].w = hi.y;
+      }
+    }
+    {
+      const int kn = min(kt + 1, n_kt - 1) * 32 + c;         // past the end: the last tile once more
+      pg = pt[min(kn >> 4, last_page)];
+      const uint8_t* kb = pool + ((size_t)pg * Hkv + kvh) * BLK + (kn & 15) * 16 + g * 256;
+#pragma unroll
+      for (int dc = 0; dc < NDC; ++dc) kf_next[dc] = *(const u32x4*)(kb + dc * 512);
+    }
     f32x16_t s;
 #pragma unroll
     for (int j = 0; j < 16; ++j) s[j] = 0.f;
 #pragma unroll
-    for (int dc = 0; dc < NDC; ++dc) {
-      const bf16x8_t kf = __builtin_bit_cast(bf16x8_t, *(const u32x4*)(kb + dc * 512));
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[dc], s, 0, 0, 0);
-    }
+    for (int dc = 0; dc < NDC; ++dc)
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[dc]), qf[dc], s, 0, 0, 0);
     // s[j] = score of key kt*32 + (j/4)*8 + g*4 + j%4 against this lane's query row
     float mx = NEG_BIG;
 #pragma unroll
@@ -432,20 +462,12 @@ __global__ __launch_bounds__(64) void k_prefill_attn(const uint8_t* __restrict__
 #pragma unroll
     for (int s2 = 0; s2 < 2; ++s2) {
       if (kt * 32 + s2 * 16 > last_key) break;          // wave-uniform: page wholly past the tile's last query
-      const int pgs = __builtin_amdgcn_readlane(pg, s2 * 16);
-      const uint8_t* vb = pool + ((size_t)pgs * Hkv + kvh) * BLK + KBYTES + g * 8;
       u32x4 pw;
       pw.x = pk[4 * s2]; pw.y = pk[4 * s2 + 1]; pw.z = pk[4 * s2 + 2]; pw.w = pk[4 * s2 + 3];
       const bf16x8_t pf = __builtin_bit_cast(bf16x8_t, pw);
 #pragma unroll
-      for (int mt = 0; mt < NMT; ++mt) {
-        const int dim = mt * 32 + c;
-        const u32x2 lo = *(const u32x2*)(vb + (size_t)dim * 16);
-        const u32x2 hi = *(const u32x2*)(vb + (size_t)(D + dim) * 16);
-        u32x4 vw;
-        vw.x = lo.x; vw.y = lo.y; vw.z = hi.x; vw.w = hi.y;
-        o[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vw), pf, o[mt], 0, 0, 0);
-      }
+      for (int mt = 0; mt < NMT; ++mt)
+        o[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vw[s2][mt]), pf, o[mt], 0, 0, 0);
     }
   }
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
