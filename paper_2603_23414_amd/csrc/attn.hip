@@ -431,34 +431,48 @@ __global__ __launch_bounds__(64) void k_prefill_attn(const uint8_t* __restrict__
 #pragma unroll
     for (int dc = 0; dc < NDC; ++dc)
       s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[dc]), qf[dc], s, 0, 0, 0);
-    // s[j] = score of key kt*32 + (j/4)*8 + g*4 + j%4 against this lane's query row
+    // s[j] = score of key kt*32 + (j/4)*8 + g*4 + j%4 against this lane's query row.  Only key tiles that reach past
+    // the tile's first query need the causal mask (the last one or two); the others are wholly visible.
+    const bool diag = kt * 32 + 31 > tile.pos0;           // wave-uniform
     float mx = NEG_BIG;
+    if (diag) {
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      const int key = kt * 32 + (j >> 2) * 8 + g * 4 + (j & 3);
-      s[j] = key <= pos_c ? s[j] * scale_log2e : NEG_BIG;
-      mx = fmaxf(mx, s[j]);
+      for (int j = 0; j < 16; ++j) {
+        const int key = kt * 32 + (j >> 2) * 8 + g * 4 + (j & 3);
+        s[j] = key <= pos_c ? s[j] * scale_log2e : NEG_BIG;
+        mx = fmaxf(mx, s[j]);
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        s[j] *= scale_log2e;
+        mx = fmaxf(mx, s[j]);
+      }
     }
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m_run, mx);
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-    m_run = m_new;
+    // the running maximum rarely moves after the first tiles: rescale the accumulators only when some row's did
+    if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      l_run *= alpha;
+#pragma unroll
+      for (int mt = 0; mt < NMT; ++mt)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) o[mt][j] *= alpha;
+      m_run = m_new;
+    }
     float ls = 0.f;
     uint32_t pk[8];
 #pragma unroll
     for (int j = 0; j < 16; j += 2) {
-      // a fully masked row (query rows past the tile's valid count never are) would give exp2(0) here; key 0 is
-      // always visible to every valid row, so m_new is a real score
-      const float p0 = s[j] > -1.0e29f ? __builtin_amdgcn_exp2f(s[j] - m_new) : 0.f;
-      const float p1 = s[j + 1] > -1.0e29f ? __builtin_amdgcn_exp2f(s[j + 1] - m_new) : 0.f;
+      // exp2 of a masked score (-1e30 - m) underflows to exactly 0; key 0 is visible to every valid row, so m_run is
+      // a real score from the first tile on
+      const float p0 = __builtin_amdgcn_exp2f(s[j] - m_run);
+      const float p1 = __builtin_amdgcn_exp2f(s[j + 1] - m_run);
       ls += p0 + p1;
       pk[j >> 1] = pack_bf2(p0, p1);
     }
-    l_run = l_run * alpha + ls;
-#pragma unroll
-    for (int mt = 0; mt < NMT; ++mt)
-#pragma unroll
-      for (int j = 0; j < 16; ++j) o[mt][j] *= alpha;
+    l_run += ls;
 #pragma unroll
     for (int s2 = 0; s2 < 2; ++s2) {
       if (kt * 32 + s2 * 16 > last_key) break;          // wave-uniform: page wholly past the tile's last query
