@@ -278,6 +278,150 @@ __global__ __launch_bounds__(256, 1) void k_gemm_bf16_deep(const uint16_t* __res
   }
 }
 
+// Variant for launches with several row blocks (prefill): a 256 x 256 workgroup tile, 2 x 2 wavefronts of 128 x 128
+// (4 x 4 MFMA tiles each), BOTH operands staged through LDS so that every fragment read feeds four MFMAs -- half the
+// LDS reads, half the global-load and LDS-write instructions per MFMA of the 256 x 128 kernels above, which is what
+// bounds those.  The packed W tiles are copied to LDS verbatim (a fragment is then one contiguous KiB); the next
+// block's global loads fly while the current one is multiplied; accumulators live in AGPRs (256 per lane).
+#define BIG_A_ELEMS (256 * LDS_ROW)
+#define BIG_W_ELEMS (8 * WTILE_ELEMS)
+#define BIG_LDS_BYTES (2 * (BIG_A_ELEMS + BIG_W_ELEMS) * 2)
+template <int EPI>
+__global__ __launch_bounds__(256, 1) void k_gemm_bf16_big(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
+                                                          float* __restrict__ C, int M, int N, int K, int kb_per_split) {
+  extern __shared__ __align__(16) uint16_t big_lds[];   // [2][A tile | W tiles]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = w & 1, wn = w >> 1;
+  const int n_base = blockIdx.x * 256;
+  const int m_base = blockIdx.y * 256;
+  const int nkb_total = K / GEMM_BK;
+  const int kb0 = blockIdx.z * kb_per_split;
+  const int nkb = min(kb_per_split, nkb_total - kb0);
+  float* __restrict__ Cz = C + (size_t)blockIdx.z * M * N;
+  // global -> LDS copy plan: 8 A chunks (rows tid/8 + 32 i, 16-byte column tid%8) and 8 W chunks (tile i, chunk tid)
+  const int a_col = tid & 7;
+  const uint16_t* a_src[8];
+  const uint16_t* w_src[8];
+  int a_dst[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int r = (tid >> 3) + i * 32;
+    a_src[i] = A + (size_t)min(m_base + r, M - 1) * K + (size_t)kb0 * GEMM_BK + a_col * 8;
+    a_dst[i] = r * LDS_ROW + a_col * 8;
+    const int nt = min(n_base + i * 32, N - 1) >> 5;             // clamped past the edge: loaded, never stored
+    w_src[i] = W + ((size_t)nt * nkb_total + kb0) * WTILE_ELEMS + tid * 8;
+  }
+  const int a_frag = (wm * 128 + (lane & 31)) * LDS_ROW + (lane >> 5) * 32;
+  const int w_frag = BIG_A_ELEMS + wn * 4 * WTILE_ELEMS + lane * 8;
+
+  f32x16_t acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) acc[i][t][j] = 0.f;
+  u32x4 areg[8], wreg[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    areg[i] = *(const u32x4*)(a_src[i]);
+    wreg[i] = *(const u32x4*)(w_src[i]);
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    *(u32x4*)&big_lds[a_dst[i]] = areg[i];
+    *(u32x4*)&big_lds[BIG_A_ELEMS + i * WTILE_ELEMS + tid * 8] = wreg[i];
+  }
+  __syncthreads();
+
+  // fragments of k-step j+1 are read while k-step j is multiplied; the global loads of the next block ride on k-steps
+  // 0 and 1, its LDS writes on k-steps 2 and 3 (into the other buffer, which every wave left at the last barrier)
+  u32x4 af[2][4], bf[2][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) af[0][i] = *(const u32x4*)(big_lds + a_frag + i * 32 * LDS_ROW);
+#pragma unroll
+  for (int t = 0; t < 4; ++t) bf[0][t] = *(const u32x4*)(big_lds + w_frag + t * WTILE_ELEMS);
+  for (int kb = 0; kb < nkb; ++kb) {
+    const int cur = kb & 1;
+    const uint16_t* buf = big_lds + cur * (BIG_A_ELEMS + BIG_W_ELEMS);
+    uint16_t* nxt = big_lds + (cur ^ 1) * (BIG_A_ELEMS + BIG_W_ELEMS);
+    const size_t k1 = (size_t)min(kb + 1, nkb - 1);           // past the end the last block is simply loaded again
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (j < 3) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) af[(j + 1) & 1][i] = *(const u32x4*)(buf + a_frag + i * 32 * LDS_ROW + (j + 1) * 8);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) bf[(j + 1) & 1][t] = *(const u32x4*)(buf + w_frag + t * WTILE_ELEMS + (j + 1) * 512);
+      }
+      if (j == 0) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) areg[i] = *(const u32x4*)(a_src[i] + k1 * GEMM_BK);
+      } else if (j == 1) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) wreg[i] = *(const u32x4*)(w_src[i] + k1 * WTILE_ELEMS);
+      } else if (j == 2) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) *(u32x4*)&nxt[a_dst[i]] = areg[i];
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) *(u32x4*)&nxt[BIG_A_ELEMS + i * WTILE_ELEMS + tid * 8] = wreg[i];
+      }
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          acc[i][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af[j & 1][i]),
+                                                              __builtin_bit_cast(bf16x8_t, bf[j & 1][t]), acc[i][t], 0, 0, 0);
+      // pin: 2 MFMA : 1 LDS read (8 of them) : 1 other memory op (8 of them), over the 16 MFMAs of the k-step
+#pragma unroll
+      for (int x = 0; x < 8; ++x) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        if (j < 3) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        if (j < 2) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        else __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    __syncthreads();
+    // first fragments of the next block (just published)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) af[0][i] = *(const u32x4*)(nxt + a_frag + i * 32 * LDS_ROW);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) bf[0][t] = *(const u32x4*)(nxt + w_frag + t * WTILE_ELEMS);
+  }
+
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int n_tile = n_base + wn * 128 + t * 32;
+    const int n_out = n_tile + (lane & 31);
+    if (EPI == 1) {
+      uint16_t* __restrict__ act = (uint16_t*)C;
+      const int F = N >> 1;
+      const int f_out = (n_tile >> 1) + (lane & 15);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          const float mine = acc[i][t][j];
+          const float other = __shfl_xor(mine, 16, 64);
+          const int mrow = m_base + wm * 128 + i * 32 + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
+          if ((lane & 16) == 0 && mrow < M && n_out < N)
+            act[(size_t)mrow * F + f_out] = f2bf(mine / (1.0f + __expf(-mine)) * other);
+        }
+    } else if (n_out < N) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          const int mrow = m_base + wm * 128 + i * 32 + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
+          if (mrow < M) Cz[(size_t)mrow * N + n_out] = acc[i][t][j];
+        }
+    }
+  }
+}
+
 // Row-major [N, K] bf16 -> packed W fragments (rows padded to a multiple of 32 must be zeroed by the caller).
 __global__ __launch_bounds__(256) void k_pack_weights(const uint16_t* __restrict__ src, uint16_t* __restrict__ dst,
                                                       size_t N, size_t K) {
@@ -335,8 +479,15 @@ static void launch_gemm_t(const uint16_t* a, const uint16_t* w, float* C, int M,
     case 2: hipLaunchKernelGGL((k_gemm_bf16<2, EPI, true>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
     case 4: hipLaunchKernelGGL((k_gemm_bf16<4, EPI, true>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
     default:
-      if (grid.y == 1) hipLaunchKernelGGL((k_gemm_bf16<8, EPI, true>), grid, dim3(256), 0, st, a, w, C, M, N, K, per);
-      else hipLaunchKernelGGL((k_gemm_bf16<8, EPI, false>), grid, dim3(256), 0, st, a, w, C, M, N, K, per);
+      if (grid.y == 1) {
+        hipLaunchKernelGGL((k_gemm_bf16<8, EPI, true>), grid, dim3(256), 0, st, a, w, C, M, N, K, per);
+      } else {   // several row blocks (prefill): 256 x 256 tiles, both operands through LDS
+        static const hipError_t attr = hipFuncSetAttribute((const void*)k_gemm_bf16_big<EPI>,
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, BIG_LDS_BYTES);
+        (void)attr;
+        hipLaunchKernelGGL((k_gemm_bf16_big<EPI>), dim3((N + 255) / 256, grid.y, S), dim3(256), BIG_LDS_BYTES, st, a, w, C,
+                           M, N, K, per);
+      }
       break;
   }
 }
