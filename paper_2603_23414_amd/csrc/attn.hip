@@ -6,16 +6,17 @@
 // row of up to four chunks leaves the kernel finished and a longer one writes one partial result per four chunks
 // (those stores are what the kernel pays most for after the K/V stream itself: about 3 us per MB of partials,
 // measured by removing them).  A row is one query token of one slot; all G query heads that share the kv head are
-// computed from a single pass over the K/V bytes.  The page layout makes both phases stream 16-byte vectors that are contiguous
-// across lanes with no LDS staging of K or V:
+// computed from a single pass over the K/V bytes.  The page layout makes both phases stream 16-byte vectors that
+// are contiguous across lanes with no LDS staging of K or V:
 //   K block [d/8][16 tokens][8 dims]  -> score phase, one lane per token (16 lanes cover one page)
 //   V block [2][d][8 tokens]          -> value phase, one lane per output dim, tokens paired for dot2
 // Scores and values use v_dot2c_f32_bf16 with the query held in scalar registers; probabilities go
 // through a 512-byte per-wave LDS tile (bf16) to be re-read as broadcast operands.  Softmax statistics
 // and accumulators are fp32.  Chunk groups of one row are merged by k_attn_merge (log-sum-exp merge).
-#define ATTN_GROUP ATTN_GROUP_CHUNKS   // chunks per workgroup
 #include "common.h"
 #include "kernels.h"
+
+#define ATTN_GROUP ATTN_GROUP_CHUNKS   // chunks per workgroup
 
 #define NEG_BIG (-1.0e30f)
 
