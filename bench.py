@@ -48,7 +48,7 @@ def device_weights(torch, m, seed):
     return blob
 
 
-def scheduler_snapshot(R, wl, L):
+def scheduler_snapshot(R, wl, L, at_step=-1):
     """Run the library's own scheduler without the model (ROLLOUT_DEBUG_NO_MODEL: same kernels, same page accounting,
     milliseconds per thousand steps) over the whole workload; return (snapshot for the warm start, full-run stats)."""
     m = wl.model
@@ -86,7 +86,7 @@ def scheduler_snapshot(R, wl, L):
     R.rollout_destroy(c)
     full["bubble_sync_baseline"] = st.idle / (wl.max_slots * st.steps)
     target = float(np.mean(ctx_sum))
-    s0 = int(np.argmin(np.abs(np.array(ctx_sum) - target)))
+    s0 = int(np.argmin(np.abs(np.array(ctx_sum) - target))) if at_step < 0 else at_step
     c = mk()
     run(c, until=s0)
     running, queued = [], []
@@ -268,6 +268,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="8b_long")
     ap.add_argument("--layers", type=int, default=0, help="debug: override the layer count (invalidates the result)")
+    ap.add_argument("--at-step", type=int, default=-1,
+                    help="debug: start the timed window from this scheduler step instead of the mean-context one "
+                         "(e.g. a late step to look at the tail drain; changes what the result means)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-attn-alone", action="store_true")
     ap.add_argument("--full-run", action="store_true",
@@ -286,7 +289,7 @@ def main():
     if args.full_run:
         return full_run(torch, R, W, wl, m, L)
     t0 = time.time()
-    snap, full = scheduler_snapshot(R, wl, L)
+    snap, full = scheduler_snapshot(R, wl, L, args.at_step)
     print(f"[bench] scheduler-only pass: {full} snapshot step {snap['step']} ({time.time() - t0:.1f}s)", file=sys.stderr)
 
     attn = None if args.no_attn_alone else attention_alone(torch, R)
