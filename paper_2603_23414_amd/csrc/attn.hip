@@ -300,7 +300,7 @@ __global__ void k_write_kv(uint8_t* __restrict__ pool, int Hkv, const uint16_t* 
 
 // ---------------------------------------------------------------------------------------------------
 int attn_supported(int head_dim, int group) {
-  return (head_dim == 128 && (group == 1 || group == 4 || group == 5)) || (head_dim == 32 && (group == 1 || group == 4));
+  return (head_dim == 128 && (group == 1 || group == 4 || group == 5)) || (head_dim == 32 && (group == 1 || group == 4 || group == 5));
 }
 
 void launch_attn_worklist(const int* row_slot, const int* row_pos, int n_rows, int4* work, int* row_wstart, int* n_work_out,
@@ -331,6 +331,7 @@ void launch_decode_attn(const AttnArgs& a, int head_dim, int group, hipStream_t 
   else if (head_dim == 128 && group == 1) launch_attn_t<128, 1>(a, st, ev0, ev1);
   else if (head_dim == 32 && group == 1) launch_attn_t<32, 1>(a, st, ev0, ev1);
   else if (head_dim == 32 && group == 4) launch_attn_t<32, 4>(a, st, ev0, ev1);
+  else if (head_dim == 32 && group == 5) launch_attn_t<32, 5>(a, st, ev0, ev1);
 }
 
 void launch_write_kv(void* pool, int Hkv, int head_dim, const void* k, const void* v, const int* tok_seq,

@@ -55,7 +55,7 @@ def _run_case(lens, Hq, Hkv, d, seed, out_fp32=True, poison=True):
 TOL = 2e-2
 
 
-@pytest.mark.parametrize("Hq,Hkv,d", [(32, 8, 128), (40, 8, 128), (4, 4, 32), (8, 8, 128), (8, 2, 32)])
+@pytest.mark.parametrize("Hq,Hkv,d", [(32, 8, 128), (40, 8, 128), (4, 4, 32), (8, 8, 128), (8, 2, 32), (10, 2, 32)])
 def test_ragged_lengths_span_pages_chunks_and_tails(Hq, Hkv, d):
     lens = [1, 2, 15, 16, 17, 63, 64, 65, 255, 256, 257, 300, 511, 513, 777, 1024, 1500]
     got, ref = _run_case(lens, Hq, Hkv, d, seed=10 + Hq)
