@@ -90,3 +90,27 @@ def test_group_boundaries_of_the_workgroup_merge(Hq, Hkv, d):
     got, ref = _run_case(lens, Hq, Hkv, d, seed=20 + Hq)
     assert np.isfinite(got).all()
     assert np.abs(got - ref).max(axis=(1, 2)).max() < TOL
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_length_mixes_and_head_layouts(seed):
+    """Row counts, head layouts and length mixes drawn at random: all-short batches, a single row, lengths that sit on
+    page / tile / chunk boundaries, and one row far longer than the rest."""
+    g = W.rng(300 + seed)
+    d = int(g.choice([32, 128]))
+    group = int(g.choice([1, 4, 5]))
+    Hkv = int(g.integers(1, 5))
+    n = int(g.integers(1, 33))
+    kind = int(g.integers(0, 4))
+    if kind == 0:
+        lens = g.integers(1, 40, n)
+    elif kind == 1:
+        lens = np.minimum(6000, np.ceil(g.lognormal(np.log(300), 1.2, n))).astype(np.int64)
+    elif kind == 2:
+        lens = g.choice([1, 15, 16, 17, 63, 64, 65, 127, 128, 129, 511, 512, 513, 1023, 1024, 1025], n)
+    else:
+        lens = g.integers(1, 200, n)
+        lens[int(g.integers(0, n))] = int(g.integers(3000, 9000))
+    got, ref = _run_case(np.maximum(1, lens), Hkv * group, Hkv, d, seed=400 + seed, out_fp32=bool(g.integers(0, 2)))
+    assert np.isfinite(got).all()
+    assert np.abs(got - ref).max() < TOL + 2e-2    # + one bf16 rounding when the output is bf16

@@ -12,6 +12,21 @@ pytestmark = pytest.mark.gpu
                                    (333, 384, 128), (333, 128, 128), (2, 256, 128), (437, 256, 64), (4096, 128, 128),
                                    (256, 4096, 192)])
 def test_gemm_matches_float64(M, N, K):
+    _check_gemm(M, N, K)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_gemm_random_shapes(seed):
+    """Row counts on both sides of every kernel variant's limits (32, 64, 128, 256 rows; several row blocks), column
+    counts that are not tile multiples, depths from one k block to a few hundred."""
+    g = W.rng(900 + seed)
+    M = int(g.choice([int(g.integers(1, 33)), int(g.integers(33, 129)), int(g.integers(129, 257)), int(g.integers(257, 1100))]))
+    N = int(g.choice([int(g.integers(1, 300)), 32 * int(g.integers(1, 40)), int(g.integers(300, 3000))]))
+    K = 64 * int(g.choice([1, 2, 3, int(g.integers(4, 40)), int(g.integers(40, 130))]))
+    _check_gemm(M, N, K)
+
+
+def _check_gemm(M, N, K):
     import torch
     import paper_2603_23414_amd as R
     g = W.rng(M * 7 + N)
