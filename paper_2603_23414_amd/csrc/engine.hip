@@ -796,10 +796,15 @@ int rollout_harvest(rollout_ctx* c, uint32_t group_size, uint32_t flags, rollout
     const int grp = c->seqs[sidx].group;
     if (grp >= 0 && --c->group_members[grp] == 0) c->free_group.push_back(grp);
   }
-  // remainder stays finished-unharvested, in its sorted order
+  // remainder stays finished-unharvested, in its sorted order; it goes through the pinned submit staging area and the
+  // engine's own stream, so the boundary kernel below is ordered after it
   const int rest = nfin - take;
-  if (rest > 0) HIPCHK(c, hipMemcpy(c->sd.fin_list, fin.data() + take, sizeof(int) * rest, hipMemcpyHostToDevice));
-  HIPCHK(c, hipMemcpy(c->sd.sc + SC_FINCOUNT, &rest, sizeof(int), hipMemcpyHostToDevice));
+  int* stage = reinterpret_cast<int*>(c->sub_host);
+  static_assert(sizeof(SubmitRec) >= 2 * sizeof(int), "staging area holds max_seqs + 1 ints");
+  memcpy(stage, fin.data() + take, sizeof(int) * rest);
+  stage[rest] = rest;
+  if (rest > 0) HIPCHK(c, hipMemcpyAsync(c->sd.fin_list, stage, sizeof(int) * rest, hipMemcpyHostToDevice, c->stream));
+  HIPCHK(c, hipMemcpyAsync(c->sd.sc + SC_FINCOUNT, stage + rest, sizeof(int), hipMemcpyHostToDevice, c->stream));
   c->n_harvested += take;
   c->n_groups_total += k;
   *n_groups = (uint32_t)k;
