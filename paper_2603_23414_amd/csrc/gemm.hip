@@ -459,6 +459,12 @@ int gemm_pick_splits(int M, int N, int K) {
   int S = 1;
   if (tiles < 192) S = M > 128 ? 256 / tiles : (256 + tiles - 1) / tiles;   // M > 128: stay within one workgroup per CU (deep kernel)
   if (S > 8) S = 8;
+  // M <= 128 runs two workgroups per CU: with a deep K (>= 32 blocks left per split) fill both slots of every CU --
+  // 280-320 workgroups leave a quarter of the CUs with twice the work (32B down projection at M = 64: 69 -> 55 us)
+  if (tiles < 192 && M <= 128) {
+    const int S2 = (512 + tiles - 1) / tiles;
+    if (S2 > S && nkb / S2 >= 32) S = S2;
+  }
   if (S > nkb / 4) S = nkb / 4 > 0 ? nkb / 4 : 1;
   const int per = (nkb + S - 1) / S;
   return (nkb + per - 1) / per;
