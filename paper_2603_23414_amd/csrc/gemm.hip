@@ -278,74 +278,91 @@ __global__ __launch_bounds__(256, 1) void k_gemm_bf16_deep(const uint16_t* __res
   }
 }
 
-// Variant for launches with several row blocks (prefill): a 256 x 256 workgroup tile, 2 x 2 wavefronts of 128 x 128
-// (4 x 4 MFMA tiles each), BOTH operands staged through LDS so that every fragment read feeds four MFMAs -- half the
-// LDS reads, half the global-load and LDS-write instructions per MFMA of the 256 x 128 kernels above, which is what
-// bounds those.  The packed W tiles are copied to LDS verbatim (a fragment is then one contiguous KiB); the next
-// block's global loads fly while the current one is multiplied; accumulators live in AGPRs (256 per lane).
+// Variant for launches with several row blocks (prefill): a 256 x (64 NT) workgroup tile, NT = 4 or 3, 2 x 2
+// wavefronts of 128 x (32 NT) (4 x NT MFMA tiles each), BOTH operands staged through LDS so that every fragment read
+// feeds several MFMAs -- half the LDS reads, half the global-load and LDS-write instructions per MFMA of the 256 x 128
+// kernels above, which is what bounds those.  The packed W tiles are copied to LDS verbatim (a fragment is then one
+// contiguous KiB); the next block's global loads fly while the current one is multiplied; accumulators live in AGPRs.
+// The 192-wide tile is for column counts that would leave the last round of 256-wide tiles half empty.
+// XMAP: workgroups go to the 8 XCDs (each with its own L2) round-robin in launch order; give every XCD a contiguous
+// run of tiles, ordered so that the 32 it runs at a time form 8 row blocks x 4 column blocks (fewer distinct operand
+// slabs per k block through that L2).
 #define BIG_A_ELEMS (256 * LDS_ROW)
-#define BIG_W_ELEMS (8 * WTILE_ELEMS)
-#define BIG_LDS_BYTES (2 * (BIG_A_ELEMS + BIG_W_ELEMS) * 2)
-template <int EPI>
+#define BIG_LDS_BYTES(NT) (2 * (BIG_A_ELEMS + 2 * (NT) * WTILE_ELEMS) * 2)
+template <int EPI, int NT, bool XMAP>
 __global__ __launch_bounds__(256, 1) void k_gemm_bf16_big(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
                                                           float* __restrict__ C, int M, int N, int K, int kb_per_split) {
   extern __shared__ __align__(16) uint16_t big_lds[];   // [2][A tile | W tiles]
+  constexpr int BUF_ELEMS = BIG_A_ELEMS + 2 * NT * WTILE_ELEMS;
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = w & 1, wn = w >> 1;
-  const int n_base = blockIdx.x * 256;
-  const int m_base = blockIdx.y * 256;
+  int tx = blockIdx.x, ty = blockIdx.y, tz = blockIdx.z;
+  if (XMAP) {
+    const int gx = gridDim.x, gy = gridDim.y, T = gx * gy * gridDim.z;
+    const int lin = blockIdx.x + gx * (blockIdx.y + gy * blockIdx.z);
+    const int xcd = lin & 7, local = lin >> 3, q = T >> 3, r = T & 7;
+    const int logical = xcd < r ? xcd * (q + 1) + local : r * (q + 1) + (xcd - r) * q + local;
+    tz = logical / (gx * gy);
+    const int id = logical - tz * gx * gy;
+    const int g = id / (8 * gx), first = g * 8, gs = min(gy - first, 8), in = id - g * 8 * gx;
+    ty = first + in % gs;
+    tx = in / gs;
+  }
+  const int n_base = tx * (64 * NT);
+  const int m_base = ty * 256;
   const int nkb_total = K / GEMM_BK;
-  const int kb0 = blockIdx.z * kb_per_split;
+  const int kb0 = tz * kb_per_split;
   const int nkb = min(kb_per_split, nkb_total - kb0);
-  float* __restrict__ Cz = C + (size_t)blockIdx.z * M * N;
-  // global -> LDS copy plan: 8 A chunks (rows tid/8 + 32 i, 16-byte column tid%8) and 8 W chunks (tile i, chunk tid)
+  float* __restrict__ Cz = C + (size_t)tz * M * N;
+  // global -> LDS copy plan: 8 A chunks (rows tid/8 + 32 i, 16-byte column tid%8) and 2 NT W chunks (tile i, chunk tid)
   const int a_col = tid & 7;
   const uint16_t* a_src[8];
-  const uint16_t* w_src[8];
+  const uint16_t* w_src[2 * NT];
   int a_dst[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int r = (tid >> 3) + i * 32;
     a_src[i] = A + (size_t)min(m_base + r, M - 1) * K + (size_t)kb0 * GEMM_BK + a_col * 8;
     a_dst[i] = r * LDS_ROW + a_col * 8;
+  }
+#pragma unroll
+  for (int i = 0; i < 2 * NT; ++i) {
     const int nt = min(n_base + i * 32, N - 1) >> 5;             // clamped past the edge: loaded, never stored
     w_src[i] = W + ((size_t)nt * nkb_total + kb0) * WTILE_ELEMS + tid * 8;
   }
   const int a_frag = (wm * 128 + (lane & 31)) * LDS_ROW + (lane >> 5) * 32;
-  const int w_frag = BIG_A_ELEMS + wn * 4 * WTILE_ELEMS + lane * 8;
+  const int w_frag = BIG_A_ELEMS + wn * NT * WTILE_ELEMS + lane * 8;
 
-  f32x16_t acc[4][4];
+  f32x16_t acc[4][NT];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < NT; ++t)
 #pragma unroll
       for (int j = 0; j < 16; ++j) acc[i][t][j] = 0.f;
-  u32x4 areg[8], wreg[8];
+  u32x4 areg[8], wreg[2 * NT];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    areg[i] = *(const u32x4*)(a_src[i]);
-    wreg[i] = *(const u32x4*)(w_src[i]);
-  }
+  for (int i = 0; i < 8; ++i) areg[i] = *(const u32x4*)(a_src[i]);
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    *(u32x4*)&big_lds[a_dst[i]] = areg[i];
-    *(u32x4*)&big_lds[BIG_A_ELEMS + i * WTILE_ELEMS + tid * 8] = wreg[i];
-  }
+  for (int i = 0; i < 2 * NT; ++i) wreg[i] = *(const u32x4*)(w_src[i]);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) *(u32x4*)&big_lds[a_dst[i]] = areg[i];
+#pragma unroll
+  for (int i = 0; i < 2 * NT; ++i) *(u32x4*)&big_lds[BIG_A_ELEMS + i * WTILE_ELEMS + tid * 8] = wreg[i];
   __syncthreads();
 
   // fragments of k-step j+1 are read while k-step j is multiplied; the global loads of the next block ride on k-steps
   // 0 and 1, its LDS writes on k-steps 2 and 3 (into the other buffer, which every wave left at the last barrier)
-  u32x4 af[2][4], bf[2][4];
+  u32x4 af[2][4], bf[2][NT];
 #pragma unroll
   for (int i = 0; i < 4; ++i) af[0][i] = *(const u32x4*)(big_lds + a_frag + i * 32 * LDS_ROW);
 #pragma unroll
-  for (int t = 0; t < 4; ++t) bf[0][t] = *(const u32x4*)(big_lds + w_frag + t * WTILE_ELEMS);
+  for (int t = 0; t < NT; ++t) bf[0][t] = *(const u32x4*)(big_lds + w_frag + t * WTILE_ELEMS);
   for (int kb = 0; kb < nkb; ++kb) {
     const int cur = kb & 1;
-    const uint16_t* buf = big_lds + cur * (BIG_A_ELEMS + BIG_W_ELEMS);
-    uint16_t* nxt = big_lds + (cur ^ 1) * (BIG_A_ELEMS + BIG_W_ELEMS);
+    const uint16_t* buf = big_lds + cur * BUF_ELEMS;
+    uint16_t* nxt = big_lds + (cur ^ 1) * BUF_ELEMS;
     const size_t k1 = (size_t)min(kb + 1, nkb - 1);           // past the end the last block is simply loaded again
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -353,34 +370,38 @@ __global__ __launch_bounds__(256, 1) void k_gemm_bf16_big(const uint16_t* __rest
 #pragma unroll
         for (int i = 0; i < 4; ++i) af[(j + 1) & 1][i] = *(const u32x4*)(buf + a_frag + i * 32 * LDS_ROW + (j + 1) * 8);
 #pragma unroll
-        for (int t = 0; t < 4; ++t) bf[(j + 1) & 1][t] = *(const u32x4*)(buf + w_frag + t * WTILE_ELEMS + (j + 1) * 512);
+        for (int t = 0; t < NT; ++t) bf[(j + 1) & 1][t] = *(const u32x4*)(buf + w_frag + t * WTILE_ELEMS + (j + 1) * 512);
       }
       if (j == 0) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) areg[i] = *(const u32x4*)(a_src[i] + k1 * GEMM_BK);
       } else if (j == 1) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) wreg[i] = *(const u32x4*)(w_src[i] + k1 * WTILE_ELEMS);
+        for (int i = 0; i < 2 * NT; ++i) wreg[i] = *(const u32x4*)(w_src[i] + k1 * WTILE_ELEMS);
       } else if (j == 2) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) *(u32x4*)&nxt[a_dst[i]] = areg[i];
       } else {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) *(u32x4*)&nxt[BIG_A_ELEMS + i * WTILE_ELEMS + tid * 8] = wreg[i];
+        for (int i = 0; i < 2 * NT; ++i) *(u32x4*)&nxt[BIG_A_ELEMS + i * WTILE_ELEMS + tid * 8] = wreg[i];
       }
 #pragma unroll
-      for (int t = 0; t < 4; ++t)
+      for (int t = 0; t < NT; ++t)
 #pragma unroll
         for (int i = 0; i < 4; ++i)
           acc[i][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af[j & 1][i]),
                                                               __builtin_bit_cast(bf16x8_t, bf[j & 1][t]), acc[i][t], 0, 0, 0);
-      // pin: 2 MFMA : 1 LDS read (8 of them) : 1 other memory op (8 of them), over the 16 MFMAs of the k-step
+      // pin the interleave over the 4 NT MFMAs of the k-step: the LDS reads (4 + NT of them) and the other memory
+      // operations (8 or 2 NT of them) are spread between pairs of MFMAs
 #pragma unroll
       for (int x = 0; x < 8; ++x) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-        if (j < 3) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        if (j < 2) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-        else __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+        if (NT == 4 || (x & 1) == 0) __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        else __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (j < 3 && x < 4 + NT) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        if (x < ((j & 1) ? 2 * NT : 8)) {
+          if (j < 2) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+          else __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+        }
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -389,12 +410,12 @@ __global__ __launch_bounds__(256, 1) void k_gemm_bf16_big(const uint16_t* __rest
 #pragma unroll
     for (int i = 0; i < 4; ++i) af[0][i] = *(const u32x4*)(nxt + a_frag + i * 32 * LDS_ROW);
 #pragma unroll
-    for (int t = 0; t < 4; ++t) bf[0][t] = *(const u32x4*)(nxt + w_frag + t * WTILE_ELEMS);
+    for (int t = 0; t < NT; ++t) bf[0][t] = *(const u32x4*)(nxt + w_frag + t * WTILE_ELEMS);
   }
 
 #pragma unroll
-  for (int t = 0; t < 4; ++t) {
-    const int n_tile = n_base + wn * 128 + t * 32;
+  for (int t = 0; t < NT; ++t) {
+    const int n_tile = n_base + wn * (32 * NT) + t * 32;
     const int n_out = n_tile + (lane & 31);
     if (EPI == 1) {
       uint16_t* __restrict__ act = (uint16_t*)C;
@@ -487,12 +508,27 @@ static void launch_gemm_t(const uint16_t* a, const uint16_t* w, float* C, int M,
     default:
       if (grid.y == 1) {
         hipLaunchKernelGGL((k_gemm_bf16<8, EPI, true>), grid, dim3(256), 0, st, a, w, C, M, N, K, per);
-      } else {   // several row blocks (prefill): 256 x 256 tiles, both operands through LDS
-        static const hipError_t attr = hipFuncSetAttribute((const void*)k_gemm_bf16_big<EPI>,
-                                                           hipFuncAttributeMaxDynamicSharedMemorySize, BIG_LDS_BYTES);
-        (void)attr;
-        hipLaunchKernelGGL((k_gemm_bf16_big<EPI>), dim3((N + 255) / 256, grid.y, S), dim3(256), BIG_LDS_BYTES, st, a, w, C,
-                           M, N, K, per);
+      } else {   // several row blocks (prefill): 256 x 256 or 256 x 192 tiles, both operands through LDS
+        // tile width: fewer rounds of 256 workgroups weighted by the width; then fewer padded columns; then the wider
+        const long long t4 = (long long)((N + 255) / 256) * grid.y * S, t3 = (long long)((N + 191) / 192) * grid.y * S;
+        const long long c4 = (t4 + 255) / 256 * 256, c3 = (t3 + 255) / 256 * 192;
+        const bool narrow = c3 < c4 || (c3 == c4 && (N + 191) / 192 * 192 < (N + 255) / 256 * 256);
+        // the XCD-aware order pays with many column tiles (gate||up: 112 of them, -7 %) and costs 2-3 % with 16
+        const int gx = narrow ? (N + 191) / 192 : (N + 255) / 256;
+        const bool xmap = gx >= 32;
+#define LAUNCH_BIG(NT_, XMAP_)                                                                                          \
+  {                                                                                                                     \
+    static const hipError_t attr = hipFuncSetAttribute((const void*)k_gemm_bf16_big<EPI, NT_, XMAP_>,                   \
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, BIG_LDS_BYTES(NT_)); \
+    (void)attr;                                                                                                         \
+    hipLaunchKernelGGL((k_gemm_bf16_big<EPI, NT_, XMAP_>), dim3(gx, grid.y, S), dim3(256), BIG_LDS_BYTES(NT_), st, a, w, C, \
+                       M, N, K, per);                                                                                   \
+  }
+        if (narrow && xmap) LAUNCH_BIG(3, true)
+        else if (narrow) LAUNCH_BIG(3, false)
+        else if (xmap) LAUNCH_BIG(4, true)
+        else LAUNCH_BIG(4, false)
+#undef LAUNCH_BIG
       }
       break;
   }
