@@ -23,6 +23,31 @@ __device__ __forceinline__ float block_sum_1024(float v, float* sh) {
   return t;
 }
 
+// t += part[0] + part[1] + .. in ascending split order (the order fixes the rounding); the loads of up to eight splits
+// are issued before the first add, so a row's split-K partials arrive in one or two memory round trips instead of S
+__device__ __forceinline__ void add_splits(float4& t, const float* __restrict__ p, size_t stride, int S) {
+  int s = 0;
+  for (; s + 8 <= S; s += 8) {
+    float4 v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = *(const float4*)(p + (size_t)(s + j) * stride);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { t.x += v[j].x; t.y += v[j].y; t.z += v[j].z; t.w += v[j].w; }
+  }
+  if (s + 4 <= S) {
+    float4 v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = *(const float4*)(p + (size_t)(s + j) * stride);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { t.x += v[j].x; t.y += v[j].y; t.z += v[j].z; t.w += v[j].w; }
+    s += 4;
+  }
+  for (; s < S; ++s) {
+    const float4 v = *(const float4*)(p + (size_t)s * stride);
+    t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
+  }
+}
+
 // h[r] += sum_s part[s][r] (S may be 0), then x[r] = bf16( h[r] * rsqrt(mean(h[r]^2) + eps) * gain ).
 // One 1024-thread block per row, 16-byte accesses; D is a multiple of 4 and at most 8192.
 __global__ __launch_bounds__(1024) void k_add_rmsnorm(float* __restrict__ h, const float* __restrict__ part, int S,
@@ -38,10 +63,7 @@ __global__ __launch_bounds__(1024) void k_add_rmsnorm(float* __restrict__ h, con
     const int c = threadIdx.x + i * 1024;
     if (c < nv) {
       float4 t = ((const float4*)(h + (size_t)r * D))[c];
-      for (int s = 0; s < S; ++s) {
-        const float4 p = ((const float4*)(part + (size_t)s * part_stride + (size_t)r * D))[c];
-        t.x += p.x; t.y += p.y; t.z += p.z; t.w += p.w;
-      }
+      add_splits(t, part + (size_t)r * D + 4 * c, part_stride, S);
       v[i] = t;
       ss += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
     }
@@ -89,12 +111,8 @@ __global__ __launch_bounds__(1024) void k_rope_kvwrite(const float* __restrict__
       const int head = e / hq4, i = (e % hq4) * 4;
       const int c1 = head * d + i, c2 = c1 + half;
       float4 x1 = make_float4(0.f, 0.f, 0.f, 0.f), x2 = x1;
-      for (int s = 0; s < S; ++s) {
-        const float4 a = *(const float4*)(src + (size_t)s * part_stride + c1);
-        const float4 b = *(const float4*)(src + (size_t)s * part_stride + c2);
-        x1.x += a.x; x1.y += a.y; x1.z += a.z; x1.w += a.w;
-        x2.x += b.x; x2.y += b.y; x2.z += b.z; x2.w += b.w;
-      }
+      add_splits(x1, src + c1, part_stride, S);
+      add_splits(x2, src + c2, part_stride, S);
       if (bias) {
         const float4 a = *(const float4*)(bias + c1), b = *(const float4*)(bias + c2);
         x1.x += a.x; x1.y += a.y; x1.z += a.z; x1.w += a.w;
@@ -122,10 +140,7 @@ __global__ __launch_bounds__(1024) void k_rope_kvwrite(const float* __restrict__
       const int ev = (e - n_rot) * 4;
       const int kvh = ev / d, dim = ev % d;
       float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-      for (int s = 0; s < S; ++s) {
-        const float4 a = *(const float4*)(src + (size_t)s * part_stride + voff + ev);
-        x.x += a.x; x.y += a.y; x.z += a.z; x.w += a.w;
-      }
+      add_splits(x, src + voff + ev, part_stride, S);
       if (bias) {
         const float4 a = *(const float4*)(bias + voff + ev);
         x.x += a.x; x.y += a.y; x.z += a.z; x.w += a.w;
