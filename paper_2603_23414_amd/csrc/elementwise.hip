@@ -200,15 +200,37 @@ __global__ __launch_bounds__(1024) void k_argmax_lse(const float* __restrict__ l
   const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
   float best = -INFINITY, mx = -INFINITY;
   int bi = 0x7fffffff;
-  for (int i = threadIdx.x; i < V; i += 1024) {
-    const float z = x[i] * scale;
+  // every thread walks its elements in ascending index order, so its first hit is its lowest index
+  auto visit = [&](int i, float xi) {
+    const float z = xi * scale;
     mx = fmaxf(mx, z);
     float v = z;
     if (sampling) {
       const float u = ((float)(philox4x32_10_word0((uint32_t)i, c1, c2, c3, k0, k1) >> 8) + 0.5f) * 5.9604644775390625e-8f;
       v = z - __logf(-__logf(u));
     }
-    if (v > best) { best = v; bi = i; }       // strided ascending: first hit is the lowest index per thread
+    if (v > best) { best = v; bi = i; }
+  };
+  const bool vec = (V & 3) == 0;     // rows are 16-byte aligned: four vectors of four logits in flight per thread
+  const int nv = V >> 2;
+  if (vec) {
+    int i = threadIdx.x;
+    for (; i + 3 * 1024 < nv; i += 4 * 1024) {
+      float4 t[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) t[j] = ((const float4*)x)[i + j * 1024];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int e = (i + j * 1024) * 4;
+        visit(e, t[j].x); visit(e + 1, t[j].y); visit(e + 2, t[j].z); visit(e + 3, t[j].w);
+      }
+    }
+    for (; i < nv; i += 1024) {
+      const float4 t = ((const float4*)x)[i];
+      visit(i * 4, t.x); visit(i * 4 + 1, t.y); visit(i * 4 + 2, t.z); visit(i * 4 + 3, t.w);
+    }
+  } else {
+    for (int i = threadIdx.x; i < V; i += 1024) visit(i, x[i]);
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
@@ -226,7 +248,23 @@ __global__ __launch_bounds__(1024) void k_argmax_lse(const float* __restrict__ l
     mx = fmaxf(mx, s_max[k]);
   }
   float sum = 0.f;
-  for (int i = threadIdx.x; i < V; i += 1024) sum += __expf(x[i] * scale - mx);
+  if (vec) {
+    int i = threadIdx.x;
+    for (; i + 3 * 1024 < nv; i += 4 * 1024) {
+      float4 t[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) t[j] = ((const float4*)x)[i + j * 1024];
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        sum += __expf(t[j].x * scale - mx) + __expf(t[j].y * scale - mx) + __expf(t[j].z * scale - mx) + __expf(t[j].w * scale - mx);
+    }
+    for (; i < nv; i += 1024) {
+      const float4 t = ((const float4*)x)[i];
+      sum += __expf(t.x * scale - mx) + __expf(t.y * scale - mx) + __expf(t.z * scale - mx) + __expf(t.w * scale - mx);
+    }
+  } else {
+    for (int i = threadIdx.x; i < V; i += 1024) sum += __expf(x[i] * scale - mx);
+  }
   sum = wave_sum(sum);
   if ((threadIdx.x & 63) == 0) s_sum[w] = sum;
   __syncthreads();
