@@ -200,15 +200,20 @@ def attention_alone(torch, R, iters=20):
                 pure_read_ceiling_gbps=float(np.median(rd[2:])))
 
 
-def full_run(torch, R, W, wl, m, L):
+def full_run(torch, R, W, wl, m, L, mode="partial"):
     """Whole job, cold start to drain: every prompt prefilled, every token decoded, harvest whenever a group is ready
-    (with the boundary work that entails), tail drain included.  Reports whole-job tokens/s and the three bubble ratios."""
+    (with the boundary work that entails), tail drain included.  Reports whole-job tokens/s and the three bubble ratios.
+    mode: "partial" (the default operating mode, with the workload's staleness bound), "onpolicy" (unfinished rollouts
+    are terminated and their tokens discarded at every update boundary) or "sync" (the canonical baseline: a batch is
+    admitted only when every slot is empty).  tokens/s counts harvested tokens only, so discarded work lowers it."""
+    mode_id = {"partial": R.ROLLOUT_MODE_PARTIAL, "onpolicy": R.ROLLOUT_MODE_ONPOLICY, "sync": R.ROLLOUT_MODE_SYNC}[mode]
+    stale = wl.max_staleness if mode == "partial" else -1
     blob = device_weights(torch, m, wl.seed_weights)
     page_bytes = wl.model.n_layers * wl.model.n_kv_heads * 2 * 16 * wl.model.head_dim * 2
     pool_bytes = wl.kv_pool_bytes or min(120 * 10**9, wl.max_slots * ((wl.prompt_len + wl.cap + 15) // 16) * page_bytes)
     cfg = R.make_cfg(m, max_slots=wl.max_slots, max_prompt_len=wl.prompt_len, max_new_tokens=wl.cap, max_seqs=wl.n_prompts,
                      kv_pool_bytes=pool_bytes * m.n_layers // wl.model.n_layers, weights_on_device=1,
-                     max_staleness=wl.max_staleness, debug_flags=R.ROLLOUT_DEBUG_TIME_ATTN)
+                     max_staleness=stale, mode=mode_id, debug_flags=R.ROLLOUT_DEBUG_TIME_ATTN)
     ctx = R.rollout_init((blob.data_ptr(), blob.numel() * 2), cfg)
     del blob
     torch.cuda.empty_cache()
@@ -241,15 +246,17 @@ def full_run(torch, R, W, wl, m, L):
     T = time.perf_counter() - t_start
     st = R.rollout_stats(ctx)
     R.rollout_destroy(ctx)
-    assert harvested == wl.n_prompts and st.gen_tokens == int(L.sum())
+    useful = int(st.gen_tokens - st.discarded_tokens)
+    assert harvested == wl.n_prompts and useful == int(L.sum())
     kvb = m.n_kv_heads * 2 * m.head_dim * 2
-    out = dict(metric=f"rollout tokens/s, whole job ({wl.name})", value=st.gen_tokens / T, unit="tokens/s", n_gpus=1,
+    out = dict(metric=f"rollout tokens/s, whole job ({wl.name}, {mode} mode)", value=useful / T, unit="tokens/s", n_gpus=1,
                steps=int(st.steps), warmup=0, ms_per_step=1e3 * T / st.steps, higher_is_better=True, scaling="weak",
                vs_baseline=None, dtype="bf16", data="synthetic",
                config=dict(workload=f"{wl.name}: whole job from a cold start to drain, {m.n_layers} layers, Q={wl.max_slots}, "
                                     f"{wl.n_prompts} prompts x {wl.prompt_len}, cap {wl.cap}, harvest {wl.harvest}, "
-                                    f"max_staleness {wl.max_staleness}",
-                           wall_s=T, gen_tokens=int(st.gen_tokens), prefill_tokens=int(st.prefill_tokens),
+                                    f"max_staleness {stale}, {mode} mode",
+                           wall_s=T, gen_tokens=int(st.gen_tokens), discarded_tokens=int(st.discarded_tokens),
+                           prefill_tokens=int(st.prefill_tokens),
                            n_stale=int(st.n_stale), n_preempt=int(st.n_preempt)),
                bubble_ratio=dict(steps=st.idle / (wl.max_slots * st.steps),
                                  steps_while_queue_non_empty=(st.idle_q / (wl.max_slots * st.steps_q)) if st.steps_q else 0.0,
@@ -276,6 +283,8 @@ def main():
     ap.add_argument("--full-run", action="store_true",
                     help="run the whole workload from a cold start to drain and report whole-job tokens/s "
                          "(minutes of GPU time; not the default bench line)")
+    ap.add_argument("--mode", choices=["partial", "onpolicy", "sync"], default="partial",
+                    help="operating mode of a --full-run (the default window always runs partial mode)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -287,7 +296,7 @@ def main():
     m = wl.model if not args.layers else wl.model.with_layers(args.layers)
     L = W.make_target_lengths(wl.n_prompts, wl.len_mu, wl.len_sigma, wl.cap, wl.seed_lengths)
     if args.full_run:
-        return full_run(torch, R, W, wl, m, L)
+        return full_run(torch, R, W, wl, m, L, args.mode)
     t0 = time.time()
     snap, full = scheduler_snapshot(R, wl, L, args.at_step)
     print(f"[bench] scheduler-only pass: {full} snapshot step {snap['step']} ({time.time() - t0:.1f}s)", file=sys.stderr)
