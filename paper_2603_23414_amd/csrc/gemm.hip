@@ -5,9 +5,10 @@
 // that: a workgroup owns 128 output columns and all (<= 256) rows; each of its 4 wavefronts owns 32 columns
 // and reads its W fragments straight from global memory in the v_mfma_f32_32x32x16_bf16 operand layout
 // (lane -> row n, 16 contiguous bytes along K), so no weight byte is loaded twice or staged through LDS.
-// Only the small activation tile A goes through LDS (double-buffered, rows padded to 144 bytes so the
-// 16-byte fragment reads are bank-conflict free).  Split-K over blockIdx.z writes fp32 partial sums that
-// the consumer kernels (residual+norm, RoPE, SiLU*mul) add up in a fixed order, so results are deterministic.
+// Only the small activation tile A goes through LDS (rows padded to 144 bytes, or xor-swizzled where the tile
+// is loaded global -> LDS directly, so that the 16-byte fragment reads are bank-conflict free).  Split-K over
+// blockIdx.z writes fp32 partial sums that the consumer kernels (residual+norm, RoPE, SiLU*mul) add up in a
+// fixed order, so results are deterministic.
 #include "common.h"
 #include "kernels.h"
 
@@ -144,137 +145,164 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16(const uint16_t* __restrict
 }
 
 // Variant for launches that cannot fill the chip twice over (<= ~1 workgroup per CU, i.e. every decode projection
-// except the LM head): one workgroup per CU gets the whole register file (accumulators move to AGPRs), the W ring
-// is 4 blocks deep, A staging runs two blocks ahead, and the A fragments of a k-step are all fetched from LDS before
-// its MFMAs issue and double-buffered across k-steps -- with a single wave per SIMD nothing else could hide those
-// latencies.  A wave owns MIW x NJ MFMA tiles; 8 x 1 (256 rows x 32 columns) is what is launched.  4 x 2 (an A
-// fragment feeds two MFMAs, half the LDS reads, W fragments fetched by two waves) measured 5-8 % slower at M = 256.
-template <int MIW, int NJ, int EPI>
+// except the LM head): one workgroup per CU gets the whole register file (accumulators in AGPRs) and 128 KiB of LDS.
+// A wave owns 8 x 1 MFMA tiles (256 rows x 32 columns).  The activation tile travels global memory -> LDS directly
+// (buffer loads with the LDS flag: no staging registers, no LDS write instructions), four 32 KiB tiles deep: block
+// kb + 3 is in flight while block kb is multiplied.  The W ring in registers runs three blocks ahead (loads complete
+// in issue order, so a deeper ring than the tiles' would buy nothing).  The MFMA stream is continuous across the
+// barrier: the next block's first fragments are read during the last k-step, and the fragments of k-step j + 1 while
+// k-step j is multiplied.  A wave's LDS-direct load fills one contiguous KiB, so the tile cannot be padded; it is
+// xor-swizzled instead: 16-byte chunk c of row r sits at chunk c ^ ((r ^ (r >> 3)) & 7) (conflict-free fragment reads).
+// The four tiles are four separate arrays on purpose: the compiler's wait-count pass tells in-flight LDS-direct loads
+// from LDS reads by the array they address, so fragment reads of one tile do not wait for the loads into another.
+#define DEEP_TILE (256 * 64)
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+template <int EPI>
 __global__ __launch_bounds__(256, 1) void k_gemm_bf16_deep(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
                                                            float* __restrict__ C, int M, int N, int K, int kb_per_split) {
-  constexpr int BM = 256;
-  constexpr int WM = 8 / MIW;          // waves along M
-  __shared__ __align__(16) uint16_t a_lds[2][BM * LDS_ROW];
+  __shared__ __align__(1024) uint16_t a0[DEEP_TILE];
+  __shared__ __align__(1024) uint16_t a1[DEEP_TILE];
+  __shared__ __align__(1024) uint16_t a2[DEEP_TILE];
+  __shared__ __align__(1024) uint16_t a3[DEEP_TILE];
+#define DEEP_SEL(b) ((b) == 0 ? a0 : (b) == 1 ? a1 : (b) == 2 ? a2 : a3)   // b is a constant after unrolling
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = w % WM, wn = w / WM;
-  const int n_base = blockIdx.x * 128 + wn * (32 * NJ);
-  const int m_base = blockIdx.y * BM;
+  const int n_base = blockIdx.x * 128 + w * 32;
+  const int m_base = blockIdx.y * 256;
   const int nkb_total = K / GEMM_BK;
   const int kb0 = blockIdx.z * kb_per_split;
   const int nkb = min(kb_per_split, nkb_total - kb0);
   float* __restrict__ Cz = C + (size_t)blockIdx.z * M * N;
-  const uint16_t* wrow[NJ];
+  // buffer descriptors: this row block of A, this wave's tile row of W (32 rows, clamped past the edge: loaded, never
+  // stored).  Every offset below stays inside them; the hardware range check is only a second line of defence.
+  const int rows_here = min(256, M - m_base);
+  const __amdgpu_buffer_rsrc_t a_rs =
+      __builtin_amdgcn_make_buffer_rsrc((void*)(A + (size_t)m_base * K), 0, rows_here * K * 2, 0x00020000);
+  const __amdgpu_buffer_rsrc_t w_rs = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)(W + (size_t)(min(n_base, N - 1) >> 5) * nkb_total * WTILE_ELEMS), 0, nkb_total * (WTILE_ELEMS * 2), 0x00020000);
+  const int w_so = kb0 * (WTILE_ELEMS * 2);
+  const int w_voff = lane * 16;
+  // A load i of wave w fills tile rows i*32 + w*8 .. +8: lane -> row l/8, physical chunk l%8 <- logical chunk
+  // (l%8) ^ f(row); rows past M are clamped to the last one (computed, never stored)
+  const int lrow = w * 8 + (lane >> 3);
+  const int a_chunk = ((lane & 7) ^ ((lrow ^ (lrow >> 3)) & 7)) * 16;      // f(row) is the same 32 rows further on
+  int a_voff[8];
 #pragma unroll
-  for (int t = 0; t < NJ; ++t)
-    wrow[t] = W + ((size_t)(min(n_base + t * 32, N - 1) >> 5) * nkb_total + kb0) * WTILE_ELEMS + lane * 8;
-  const int a_col = tid & 7;
-  const uint16_t* a_src[8];
-  int a_dst[8];
+  for (int i = 0; i < 8; ++i) a_voff[i] = min(i * 32 + lrow, rows_here - 1) * K * 2 + a_chunk;
+  const int a_so = kb0 * (GEMM_BK * 2);
+#define DEEP_LDA(buf, i, kb_)                                                                                     \
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rs, (lds_ptr_t)(DEEP_SEL(buf) + ((i) * 32 + w * 8) * 64), 16, a_voff[i], \
+                                           a_so + (kb_) * (GEMM_BK * 2), 0, 0)
+#define DEEP_LDW(kb_, j) __builtin_amdgcn_raw_buffer_load_b128(w_rs, w_voff, w_so + (kb_) * (WTILE_ELEMS * 2) + (j) * 1024, 2)
+#define DEEP_MFMA8(AF, BF)                                                                                        \
+  _Pragma("unroll") for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                  \
+      __builtin_bit_cast(bf16x8_t, AF[i]), BF, acc[i], 0, 0, 0)
+  // pin the interleave of a k-step: one LDS read and (with_mem) one global load per MFMA or per second MFMA
+#define DEEP_PIN(mem_every)                                                                                       \
+  _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                                  \
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                                             \
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                             \
+    if ((mem_every) == 1 || ((mem_every) == 2 && (i & 1))) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);      \
+  }                                                                                                                \
+  __builtin_amdgcn_sched_barrier(0);
+  // fragment read: row (lane & 31) + 32 i, logical chunk (lane >> 5) * 4 + j
+  const int frow = lane & 31;
+  const int ff = (frow ^ (frow >> 3)) & 7;
+  int a_frag[4];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int r = (tid >> 3) + i * 32;
-    a_src[i] = A + (size_t)min(m_base + r, M - 1) * K + (size_t)kb0 * GEMM_BK + a_col * 8;
-    a_dst[i] = r * LDS_ROW + a_col * 8;
-  }
-  const int a_frag = (wm * (32 * MIW) + (lane & 31)) * LDS_ROW + (lane >> 5) * 32;
-
-  f32x16_t acc[MIW][NJ];
+  for (int j = 0; j < 4; ++j) a_frag[j] = frow * 64 + ((((lane >> 5) * 4 + j) ^ ff) * 8);
+  f32x16_t acc[8];
 #pragma unroll
-  for (int i = 0; i < MIW; ++i)
+  for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int t = 0; t < NJ; ++t)
+    for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+  u32x4 breg[4][4];   // W ring; every index is a compile-time constant after unrolling
+  u32x4 af[2][8];     // A fragments of the current and the next k-step
+  // prologue: A blocks 0..2 into tiles 0..2, W blocks 0..2 (past the end the last block is simply loaded again)
 #pragma unroll
-      for (int j = 0; j < 16; ++j) acc[i][t][j] = 0.f;
-
-  u32x4 breg[4][NJ][4];  // W ring: block kb + 3 is in flight while block kb is multiplied
-  u32x4 areg[2][8];      // A staging: block kb + 2 is in flight, block kb + 1 goes to LDS at the end of block kb
-  u32x4 af[2][MIW];      // A fragments of the current and the next k-step
+  for (int b = 0; b < 3; ++b)
 #pragma unroll
-  for (int i = 0; i < 8; ++i) areg[0][i] = *(const u32x4*)(a_src[i]);
-  {
-    const size_t k1 = (size_t)min(1, nkb - 1) * GEMM_BK;
+    for (int i = 0; i < 8; ++i) DEEP_LDA(b, i, min(b, nkb - 1));
 #pragma unroll
-    for (int i = 0; i < 8; ++i) areg[1][i] = *(const u32x4*)(a_src[i] + k1);
-  }
+  for (int r = 0; r < 3; ++r)
 #pragma unroll
-  for (int r = 0; r < 3; ++r) {
-    const size_t wr = (size_t)min(r, nkb - 1) * WTILE_ELEMS;
-#pragma unroll
-    for (int t = 0; t < NJ; ++t)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) breg[r][t][j] = __builtin_nontemporal_load((const u32x4*)(wrow[t] + wr + j * 512));
-  }
-#pragma unroll
-  for (int i = 0; i < 8; ++i) *(u32x4*)&a_lds[0][a_dst[i]] = areg[0][i];
+    for (int j = 0; j < 4; ++j) breg[r][j] = DEEP_LDW(min(r, nkb - 1), j);
+  __builtin_amdgcn_s_waitcnt(0x0F70 | 12);   // vmcnt(12): the 24 A loads have landed, the 12 W loads may still fly
   __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 8; ++i) af[0][i] = *(const u32x4*)(a0 + a_frag[0] + i * 32 * 64);
 
   for (int kbase = 0; kbase < nkb; kbase += 4) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int kb = kbase + u;
       if (kb < nkb) {                                    // uniform
-        const int cur = kb & 1;
-        const size_t k2 = (size_t)min(kb + 2, nkb - 1) * GEMM_BK, w3 = (size_t)min(kb + 3, nkb - 1) * WTILE_ELEMS;
+        const uint16_t* al = DEEP_SEL(u % 4);
+        const uint16_t* al_next = DEEP_SEL((u + 1) % 4);
+        const int k3 = min(kb + 3, nkb - 1);
+        // k-step 0: + A block kb+3 straight into tile (kb+3) % 4 (last read before the previous barrier)
 #pragma unroll
-        for (int i = 0; i < 8; ++i) areg[u & 1][i] = *(const u32x4*)(a_src[i] + k2);
+        for (int i = 0; i < 8; ++i) af[1][i] = *(const u32x4*)(al + a_frag[1] + i * 32 * 64);
+        DEEP_MFMA8(af[0], __builtin_bit_cast(bf16x8_t, breg[u % 4][0]));
 #pragma unroll
-        for (int t = 0; t < NJ; ++t)
+        for (int i = 0; i < 8; ++i) DEEP_LDA((u + 3) % 4, i, k3);
+        DEEP_PIN(1)
+        // k-step 1
 #pragma unroll
-          for (int j = 0; j < 4; ++j) breg[(u + 3) & 3][t][j] = __builtin_nontemporal_load((const u32x4*)(wrow[t] + w3 + j * 512));
-        const uint16_t* al = a_lds[cur] + a_frag;
+        for (int i = 0; i < 8; ++i) af[0][i] = *(const u32x4*)(al + a_frag[2] + i * 32 * 64);
+        DEEP_MFMA8(af[1], __builtin_bit_cast(bf16x8_t, breg[u % 4][1]));
+        DEEP_PIN(0)
+        // k-step 2: + W block kb+3
 #pragma unroll
-        for (int i = 0; i < MIW; ++i) af[0][i] = *(const u32x4*)(al + i * 32 * LDS_ROW);
+        for (int i = 0; i < 8; ++i) af[1][i] = *(const u32x4*)(al + a_frag[3] + i * 32 * 64);
+        DEEP_MFMA8(af[0], __builtin_bit_cast(bf16x8_t, breg[u % 4][2]));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) breg[(u + 3) % 4][j] = DEEP_LDW(k3, j);
+        DEEP_PIN(2)
+        // k-step 3: first fragments of block kb+1 (published one barrier ago)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) af[0][i] = *(const u32x4*)(al_next + a_frag[0] + i * 32 * 64);
+        DEEP_MFMA8(af[1], __builtin_bit_cast(bf16x8_t, breg[u % 4][3]));
+        DEEP_PIN(0)
+        // block kb+2 (its A loads were issued one iteration ago) must have landed before this barrier publishes it;
+        // only this iteration's 8 A + 4 W loads are newer
+        __builtin_amdgcn_s_waitcnt(0x0F70 | 12);
+        __builtin_amdgcn_s_barrier();          // no fence: a release fence would wait for this iteration's loads too
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          if (j < 3) {
-#pragma unroll
-            for (int i = 0; i < MIW; ++i) af[(j + 1) & 1][i] = *(const u32x4*)(al + i * 32 * LDS_ROW + (j + 1) * 8);
-          }
-#pragma unroll
-          for (int t = 0; t < NJ; ++t) {
-            const bf16x8_t bf = __builtin_bit_cast(bf16x8_t, breg[u][t][j]);
-#pragma unroll
-            for (int i = 0; i < MIW; ++i)
-              acc[i][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af[j & 1][i]), bf,
-                                                                  acc[i][t], 0, 0, 0);
-          }
-          __builtin_amdgcn_sched_barrier(0);
-        }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) *(u32x4*)&a_lds[cur ^ 1][a_dst[i]] = areg[(u + 1) & 1][i];
-        __syncthreads();
       }
     }
   }
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // the redundant loads past the last block have landed before LDS is given up
+#undef DEEP_PIN
+#undef DEEP_MFMA8
+#undef DEEP_LDW
+#undef DEEP_LDA
+#undef DEEP_SEL
 
+  // C fragment: element j of lane -> row (j/4)*8 + (lane/32)*4 + j%4, col lane%32
+  const int n_out = n_base + (lane & 31);
+  if (EPI == 1) {
+    uint16_t* __restrict__ act = (uint16_t*)C;
+    const int F = N >> 1;
+    const int f_out = (n_base >> 1) + (lane & 15);
 #pragma unroll
-  for (int t = 0; t < NJ; ++t) {
-    const int n_out = n_base + t * 32 + (lane & 31);
-    if (EPI == 1) {
-      uint16_t* __restrict__ act = (uint16_t*)C;
-      const int F = N >> 1;
-      const int f_out = ((n_base + t * 32) >> 1) + (lane & 15);
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
-      for (int i = 0; i < MIW; ++i)
+      for (int j = 0; j < 16; ++j) {
+        const float mine = acc[i][j];
+        const float other = __shfl_xor(mine, 16, 64);
+        const int mrow = m_base + i * 32 + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
+        if ((lane & 16) == 0 && mrow < M && n_out < N)
+          act[(size_t)mrow * F + f_out] = f2bf(mine / (1.0f + __expf(-mine)) * other);
+      }
+  } else if (n_out < N) {
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-          const float mine = acc[i][t][j];
-          const float other = __shfl_xor(mine, 16, 64);
-          const int mrow = m_base + wm * (32 * MIW) + i * 32 + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
-          if ((lane & 16) == 0 && mrow < M && n_out < N)
-            act[(size_t)mrow * F + f_out] = f2bf(mine / (1.0f + __expf(-mine)) * other);
-        }
-    } else if (n_out < N) {
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
-      for (int i = 0; i < MIW; ++i)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-          const int mrow = m_base + wm * (32 * MIW) + i * 32 + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
-          if (mrow < M) Cz[(size_t)mrow * N + n_out] = acc[i][t][j];
-        }
-    }
+      for (int j = 0; j < 16; ++j) {
+        const int mrow = m_base + i * 32 + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
+        if (mrow < M) Cz[(size_t)mrow * N + n_out] = acc[i][j];
+      }
   }
 }
 
@@ -498,7 +526,7 @@ static void launch_gemm_t(const uint16_t* a, const uint16_t* w, float* C, int M,
   const int mi = M <= 32 ? 1 : M <= 64 ? 2 : M <= 128 ? 4 : 8;
   dim3 grid((N + 127) / 128, (M + 32 * mi - 1) / (32 * mi), S);
   if (mi == 8 && (long long)grid.x * grid.y * grid.z <= 256) {   // at most one workgroup per CU: the deep variant
-    hipLaunchKernelGGL((k_gemm_bf16_deep<8, 1, EPI>), grid, dim3(256), 0, st, a, w, C, M, N, K, per);
+    hipLaunchKernelGGL((k_gemm_bf16_deep<EPI>), grid, dim3(256), 0, st, a, w, C, M, N, K, per);
     return;
   }
   switch (mi) {   // a single row block (every decode launch) streams W; several row blocks share it through L2
