@@ -121,7 +121,7 @@ typedef struct rollout_stats_t {
  *   wo[D,Hq*d], ffn_norm[D], w_gate[F,D], w_up[F,D], w_down[D,F] }, final_norm[D], lm_head[V,D],
  * every matrix row-major [out, in].  The blob is copied (and repacked) before the call returns.
  * Errors: EINVAL (null / unsupported shape: head_dim must be 32 or 128, Hq/Hkv in {1,4,5}, page_tokens 16,
- * max_slots <= 1024, d_model, d_ffn multiples of 64), ENOMEM, EDEVICE. */
+ * max_slots <= 1024, d_model, d_ffn multiples of 64, d_model <= 8192, d_ffn <= 2^20, vocab <= 2^24), ENOMEM, EDEVICE. */
 int rollout_init(rollout_ctx** out, const void* weights, size_t weights_bytes, const rollout_cfg* cfg);
 
 /* Sec. 3.2 / Sec. 3.3: install the policy produced by the trainer's update (same shape, same blob format and location
@@ -229,7 +229,8 @@ int rollout_attn_decode(const void* pool_dev, uint32_t n_q_heads, uint32_t n_kv_
 /* ---- the bf16 MFMA projection GEMM alone: c[M,N] (fp32) = a[M,K] (bf16, row-major) * w[N,K]^T (bf16) ----
  * The kernels read w in a packed fragment layout (tiles of 32 rows x 64 columns stored in the order the MFMA
  * operand loads consume them, rows padded to a multiple of 32); rollout_gemm_pack_weights converts a row-major
- * [N, K] matrix into rollout_gemm_packed_bytes(N, K) bytes at packed_dev.  K must be a multiple of 64.
+ * [N, K] matrix into rollout_gemm_packed_bytes(N, K) bytes at packed_dev.  K must be a multiple of 64, K <= 2^20,
+ * M and N <= 2^24 (EINVAL otherwise).
  * workspace_dev needs rollout_gemm_workspace_bytes(M, N, K) bytes.  All calls only enqueue on `stream`. */
 uint64_t rollout_gemm_packed_bytes(uint32_t N, uint32_t K);
 int rollout_gemm_pack_weights(const void* w_dev, void* packed_dev, uint32_t N, uint32_t K, void* stream);

@@ -449,8 +449,10 @@ int rollout_init(rollout_ctx** out, const void* weights, size_t weights_bytes, c
     return fail(nullptr, ROLLOUT_EINVAL, "unsupported head_dim / query-group size (head_dim 32 or 128, group 1, 4 or 5)");
   if (f.page_tokens != PAGE_TOKENS) return fail(nullptr, ROLLOUT_EINVAL, "page_tokens must be 16");
   if (f.max_slots == 0 || f.max_slots > 1024) return fail(nullptr, ROLLOUT_EINVAL, "max_slots must be in 1..1024");
-  if (f.d_model % 64 || f.d_ffn % 64 || (f.n_q_heads * f.head_dim) % 64 || f.d_model > 8192)
-    return fail(nullptr, ROLLOUT_EINVAL, "d_model, d_ffn and n_q_heads*head_dim must be multiples of 64; d_model <= 8192");
+  if (f.d_model % 64 || f.d_ffn % 64 || (f.n_q_heads * f.head_dim) % 64 || f.d_model > 8192 || f.d_ffn > (1u << 20) ||
+      f.vocab > (1u << 24))
+    return fail(nullptr, ROLLOUT_EINVAL,
+                "d_model, d_ffn and n_q_heads*head_dim must be multiples of 64; d_model <= 8192, d_ffn <= 2^20, vocab <= 2^24");
   if (f.max_prompt_len == 0 || f.max_new_tokens == 0 || f.max_seqs == 0)
     return fail(nullptr, ROLLOUT_EINVAL, "max_prompt_len, max_new_tokens and max_seqs must be positive");
   if (f.eos_id < 0 || (uint32_t)f.eos_id >= f.vocab) return fail(nullptr, ROLLOUT_EINVAL, "eos_id outside the vocabulary");
@@ -1026,6 +1028,8 @@ int rollout_gemm_bf16(const void* a_dev, const void* w_packed_dev, float* c_dev,
                       void* workspace_dev, uint64_t workspace_bytes, void* stream) {
   if (!a_dev || !w_packed_dev || !c_dev || M == 0 || N == 0 || K == 0) return fail(nullptr, ROLLOUT_EINVAL, "null argument");
   if (K % 64) return fail(nullptr, ROLLOUT_EINVAL, "K must be a multiple of 64");
+  if (K > (1u << 20) || M > (1u << 24) || N > (1u << 24))   // byte offsets inside one row block / tile row are 32-bit
+    return fail(nullptr, ROLLOUT_EINVAL, "matrix too large (K <= 2^20, M and N <= 2^24)");
   const int S = gemm_pick_splits((int)M, (int)N, (int)K);
   if (S == 1) {
     launch_gemm(a_dev, w_packed_dev, c_dev, (int)M, (int)N, (int)K, 1, (hipStream_t)stream);

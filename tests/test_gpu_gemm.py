@@ -47,3 +47,14 @@ def _check_gemm(M, N, K):
     # products of bf16 are exact in fp32; only the fp32 accumulation order differs: ~K^0.5 * 2^-24 * |terms|
     scale = np.sqrt(K) * 0.05
     assert np.abs(got - ref).max() < 1e-4 * scale + 1e-6
+
+
+def test_gemm_rejects_sizes_whose_offsets_would_not_fit_32_bits():
+    import torch
+    import paper_2603_23414_amd as R
+    t = torch.zeros(64, dtype=torch.int16, device="cuda:0")
+    c = torch.zeros(64, dtype=torch.float32, device="cuda:0")
+    for M, N, K in [(1, 32, (1 << 20) + 64), ((1 << 24) + 1, 32, 64), (1, (1 << 24) + 1, 64), (1, 32, 100)]:
+        with pytest.raises(R.RolloutError) as e:
+            R.rollout_gemm_bf16(t.data_ptr(), t.data_ptr(), c.data_ptr(), M, N, K, t.data_ptr(), 0)
+        assert e.value.code == -1      # EINVAL
