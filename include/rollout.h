@@ -70,7 +70,7 @@ typedef struct rollout_cfg {
   uint64_t page_seed;         /* seeds the initial order of the page free list */
   int32_t device;             /* HIP device ordinal */
   uint32_t reserved;
-  /* sampling (Sec. 4.1 collects several sampled responses per prompt: submit the prompt once per response) */
+  /* sampling (Sec. 4.1 collects several sampled responses per prompt: rollout_submit_n) */
   float temperature;          /* 0 = greedy argmax; > 0 = draw from softmax(logits / temperature) by Gumbel-max */
   uint32_t reserved2;
   uint64_t sample_seed;       /* key of the counter-based generator; the counter is (vocab index, token index, seq_id) */
