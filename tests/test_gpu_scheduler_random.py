@@ -120,3 +120,42 @@ def test_random_case_bit_exact(seed):
         drive(c, orc, (R, ctx))
     finally:
         R.rollout_destroy(ctx)
+
+
+@pytest.mark.gpu
+def test_two_engines_side_by_side_do_not_disturb_each_other():
+    """Two contexts with different shapes of work and operating modes, stepped alternately: each still
+    agrees with its own oracle, so the library keeps no state outside its contexts."""
+    import paper_2603_23414_amd as R
+    ca, cb = draw_case(3), draw_case(11)
+    oa, ob = oracle_for(ca), oracle_for(cb)
+
+    def mk(c):
+        return make_engine(SHAPE, None, max_slots=c["Q"], max_prompt_len=c["P"], cap=c["cap"], max_seqs=c["n"] * c["k"],
+                           kv_pool_bytes=c["pool_pages"] * PAGE_BYTES, mode=c["mode"], max_staleness=c["stale"],
+                           page_seed=c["page_seed"], debug_flags=R.ROLLOUT_DEBUG_NO_MODEL)
+
+    xa, xb = mk(ca), mk(cb)
+    try:
+        for c, o, x in ((ca, oa, xa), (cb, ob, xb)):
+            toks, offs = flat_prompts(c["prompts"])
+            assert R.rollout_submit_n(x, toks, offs, c["L"], c["k"]) == o.submit(c["prompts"], c["L"], n_responses=c["k"])
+        live = [(ca, oa, xa), (cb, ob, xb)]
+        while live:
+            for c, o, x in list(live):
+                if not (o.queue or any(s is not None for s in o.slots)):
+                    live.remove((c, o, x))
+                    continue
+                assert info_tuple(R.rollout_step(x)) == info_tuple(o.step())
+                if len(o.finished) >= c["G"]:
+                    _harvest_both(R, x, o, c["G"])
+        for c, o, x in ((ca, oa, xa), (cb, ob, xb)):
+            while o.finished or o.queue or any(s is not None for s in o.slots):
+                if o.queue or any(s is not None for s in o.slots):
+                    assert info_tuple(R.rollout_step(x)) == info_tuple(o.step())
+                else:
+                    _harvest_both(R, x, o, c["G"], flush=True)
+            _compare_stats(R, x, o)
+    finally:
+        R.rollout_destroy(xa)
+        R.rollout_destroy(xb)
