@@ -172,8 +172,9 @@ class OracleModel:
 
 
 def greedy_token(logits: np.ndarray) -> int:
-    """argmax with the lowest index winning ties."""
-    return int(np.argmax(logits))
+    """argmax with the lowest index winning ties; the logits are compared as binary32 values (the precision the
+    engine's logits have), so two entries that round to the same binary32 number tie."""
+    return int(np.argmax(np.asarray(logits, dtype=np.float32)))
 
 
 def log_prob(logits: np.ndarray, tok: int) -> float:

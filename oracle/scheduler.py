@@ -56,16 +56,21 @@ EOS_FORCED_ONLY, EOS_NATURAL_OR_FORCED = 0, 1
 _M64 = (1 << 64) - 1
 
 
+def splitmix64_next(state: int):
+    """One step of splitmix64 (Steele, Lea, Flood 2014): returns (new state, 64-bit output)."""
+    state = (state + 0x9E3779B97F4A7C15) & _M64
+    z = state
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & _M64
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & _M64
+    return state, z ^ (z >> 31)
+
+
 def splitmix64_permutation(n: int, seed: int) -> List[int]:
-    """Fisher-Yates shuffle of 0..n-1 driven by the splitmix64 sequence (Steele et al. 2014)."""
+    """Fisher-Yates shuffle of 0..n-1, from the top down, position i swapped with (next splitmix64 output) mod (i+1)."""
     state = seed & _M64
     perm = list(range(n))
     for i in range(n - 1, 0, -1):
-        state = (state + 0x9E3779B97F4A7C15) & _M64
-        z = state
-        z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & _M64
-        z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & _M64
-        z ^= z >> 31
+        state, z = splitmix64_next(state)
         j = z % (i + 1)
         perm[i], perm[j] = perm[j], perm[i]
     return perm
@@ -96,6 +101,7 @@ class Seq:
         self.slot = -1
         self.state = QUEUED
         self.completion_step = -1
+        self.policy_version = 0   # policy version under which the last token was produced (set at finish)
         self.kv_version = 0
         self.n_preempt = 0
         self.pages: List[int] = []
@@ -261,6 +267,7 @@ class OracleRollout:
                 or s.gen_len >= self.cap
             if fin:
                 s.completion_step = self.step_no
+                s.policy_version = self.version
                 s.state = FINISHED
                 self.finished.append(s)
                 self._release(s)

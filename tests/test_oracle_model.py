@@ -274,6 +274,24 @@ def test_log_prob_is_log_of_softmax_and_greedy_is_max_prob():
     assert 0 < math.exp(log_prob(lg, int(np.argmax(lg)))) <= 1
 
 
+def test_greedy_token_ties_go_to_the_lowest_index():
+    """Exact ties at the maximum: inside one run of positions, far apart, at both ends, everywhere; and entries that
+    differ only below binary32 resolution tie as well (logits are compared as fp32)."""
+    from oracle import greedy_token
+    x = np.array([0.5, 2.0, -1.0, 2.0, 2.0, 1.0])
+    assert greedy_token(x) == 1
+    assert greedy_token(x[::-1].copy()) == 1               # reversed: maxima at 1, 2, 4
+    y = np.full(5000, -3.0)
+    y[[4096, 17]] = 7.25
+    assert greedy_token(y) == 17
+    y[0] = y[4999] = 7.25
+    assert greedy_token(y) == 0
+    assert greedy_token(np.zeros(33)) == 0
+    assert greedy_token(np.array([1.0, 3.0, 3.0 + 1e-12, 2.0])) == 1      # equal after rounding to binary32
+    assert greedy_token(np.array([1.0, 3.0, 3.0 + 1e-6, 2.0])) == 2       # distinct in binary32
+    assert greedy_token(np.array([-np.inf, -5.0, -5.0])) == 1
+
+
 def test_float32_oracle_tracks_float64():
     m, w = _tiny(seed=5)
     toks = list(_r(14).integers(0, m.vocab, 12))

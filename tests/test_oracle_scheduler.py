@@ -169,6 +169,24 @@ def test_on_policy_mode_discards_unfinished_tokens_at_each_boundary():
     assert st["gen_tokens"] == int(L.sum()) + st["discarded_tokens"]
 
 
+def test_policy_version_tells_which_update_a_finished_rollout_predates():
+    """Hand-built: Q = 4, lengths 2, 2, 2, 6, groups of 2.  Three rollouts finish in step 1 under policy version 0;
+    the harvest after that step feeds two of them (one update: version 1) and carries the third, which is fed with
+    the long one only at the end -- its record still says version 0, so the trainer can see it predates the update.
+    In on-policy mode the long rollout is terminated at the boundary and regenerated under version 1."""
+    for mode in (MODE_PARTIAL, MODE_ONPOLICY):
+        o = _mk([2, 2, 2, 6], Q=4, mode=mode)
+        o.step(); o.step()
+        g = o.harvest(2)
+        assert [[s.seq_id for s in x] for x in g] == [[0, 1]] and o.version == 1
+        assert [s.policy_version for s in g[0]] == [0, 0]
+        groups = o.run_to_completion(2)
+        assert [[s.seq_id for s in x] for x in groups] == [[2, 3]]
+        assert [s.policy_version for s in groups[0]] == [0, 1]
+        assert o.seqs[3].completion_step == (5 if mode == MODE_PARTIAL else 2 + 6 - 1)
+        assert all(s.policy_version <= o.version for s in o.seqs)
+
+
 def test_micro_curriculum_completion_steps_non_decreasing_across_groups():
     L = _lengths(256, 9)
     o = _mk(L, Q=32)
@@ -183,17 +201,27 @@ def test_micro_curriculum_completion_steps_non_decreasing_across_groups():
 def test_splitmix64_permutation_is_a_permutation_and_matches_published_first_outputs():
     p = splitmix64_permutation(1000, 42)
     assert sorted(p) == list(range(1000)) and p != list(range(1000))
-    # first three splitmix64 outputs for seed 1234567 as listed with the reference C code
+    # the generator the oracle's shuffle draws from, called through the oracle's own function: the first three outputs
+    # for seed 1234567 are the values listed with the published C code
     import oracle.scheduler as S
     st, outs = 1234567, []
     for _ in range(3):
-        st = (st + 0x9E3779B97F4A7C15) & S._M64
-        z = st
-        z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & S._M64
-        z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & S._M64
-        outs.append(z ^ (z >> 31))
+        st, z = S.splitmix64_next(st)
+        outs.append(z)
     assert outs == [6457827717110365317, 3203168211198807973, 9817491932198370423]
-    assert splitmix64_permutation(5, 7) == splitmix64_permutation(5, 7)
+    assert st == (1234567 + 3 * 0x9E3779B97F4A7C15) % (1 << 64)
+    # the shuffle itself against a brute-force replay of its definition (top-down Fisher-Yates on those outputs)
+    for n, seed in [(5, 7), (17, 0), (64, 1234567)]:
+        ref, st = list(range(n)), seed
+        for i in range(n - 1, 0, -1):
+            st, z = S.splitmix64_next(st)
+            j = z % (i + 1)
+            ref[i], ref[j] = ref[j], ref[i]
+        assert splitmix64_permutation(n, seed) == ref
+    # known answer for a 3-element shuffle worked by hand from the published outputs above: i = 2 swaps with
+    # 6457827717110365317 % 3 = 0 -> [2, 1, 0]; i = 1 swaps with 3203168211198807973 % 2 = 1 -> unchanged
+    assert 6457827717110365317 % 3 == 0 and 3203168211198807973 % 2 == 1
+    assert splitmix64_permutation(3, 1234567) == [2, 1, 0]
 
 
 def test_natural_eos_and_model_driven_rollout_tiny():
