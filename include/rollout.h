@@ -98,7 +98,8 @@ typedef struct rollout_traj {
   uint32_t group_idx;        /* running index of the update group this record belongs to */
   uint64_t tok_off;          /* offset of its gen_len tokens (and log-probs) in tok_buf / logp_buf */
   uint32_t n_preempt;
-  uint32_t reserved;
+  uint32_t policy_version;   /* update boundaries (policy versions) passed when its last token was produced; compare with
+                                rollout_stats_t.version at the harvest to see how stale a finished rollout is */
 } rollout_traj;
 
 typedef struct rollout_stats_t {
@@ -237,6 +238,23 @@ int rollout_gemm_pack_weights(const void* w_dev, void* packed_dev, uint32_t N, u
 uint64_t rollout_gemm_workspace_bytes(uint32_t M, uint32_t N, uint32_t K);
 int rollout_gemm_bf16(const void* a_dev, const void* w_packed_dev, float* c_dev, uint32_t M, uint32_t N, uint32_t K,
                       void* workspace_dev, uint64_t workspace_bytes, void* stream);
+
+/* The gate/up projection with its SwiGLU epilogue alone (the largest weight stream of a decode step, Sec. 2.2):
+ * act[M, F] (bf16) = silu(a Wg^T) * (a Wu^T), a bf16 [M, K].  w_packed_dev is rollout_gemm_pack_weights applied to the
+ * [2F, K] matrix whose rows interleave gate and up in blocks of 16: rows 32q .. 32q+15 = Wg rows 16q .. 16q+15,
+ * rows 32q+16 .. 32q+31 = Wu rows 16q .. 16q+15 (so one wavefront's 32 output columns hold gate and up of the same
+ * 16 features).  F must be a multiple of 16, K of 64.  Enqueue only; needs no workspace. */
+int rollout_gemm_swiglu_bf16(const void* a_dev, const void* w_packed_dev, void* act_dev, uint32_t M, uint32_t F, uint32_t K,
+                             void* stream);
+
+/* Name of the kernel instantiation rollout_gemm_bf16 (swiglu = 0; N output columns) or rollout_gemm_swiglu_bf16
+ * (swiglu = 1; N = 2F) launches for this shape, e.g. "k_gemm_bf16_deep<1>"; the engine's projections go through the
+ * same selection, so a parity test can state which instantiation it covers.  splits = the number of K splits
+ * (0 = what rollout_gemm_bf16 picks, i.e. rollout_gemm_splits; the engine uses that for the QKV, O and down
+ * projections and 1 for the LM head; ignored with swiglu).  Library-owned, thread-local string, valid until the
+ * next call; "" (resp. 0) for an unsupported shape. */
+const char* rollout_gemm_kernel_name(uint32_t M, uint32_t N, uint32_t K, uint32_t splits, int swiglu);
+uint32_t rollout_gemm_splits(uint32_t M, uint32_t N, uint32_t K);
 
 /* ---- plain streaming kernels: dst = src, and a pure read of src (16-byte accesses, grid-stride).  They exist to
  * calibrate the memory-traffic counters against a known byte count and to measure the practical HBM ceiling that the

@@ -17,7 +17,8 @@ __all__ = [
     "rollout_attn_pool_bytes", "rollout_attn_write_kv", "rollout_attn_workspace_bytes", "rollout_attn_plan",
     "rollout_attn_decode", "rollout_gemm_workspace_bytes", "rollout_gemm_bf16", "rollout_stream_copy",
     "rollout_stream_read", "rollout_gemm_packed_bytes", "rollout_gemm_pack_weights", "rollout_update_weights",
-    "rollout_submit_n", "make_cfg",
+    "rollout_submit_n", "rollout_gemm_swiglu_bf16", "rollout_gemm_kernel_name", "rollout_gemm_splits",
+    "make_cfg",
     "ROLLOUT_FLUSH", "ROLLOUT_DEBUG_NO_MODEL", "ROLLOUT_DEBUG_TIME_ATTN", "ROLLOUT_MODE_PARTIAL",
     "ROLLOUT_MODE_ONPOLICY", "ROLLOUT_MODE_SYNC", "ROLLOUT_EOS_FORCED_ONLY", "ROLLOUT_EOS_NATURAL_OR_FORCED",
     "EXPORTS",
@@ -41,6 +42,7 @@ EXPORTS = [
     "rollout_attn_write_kv", "rollout_attn_workspace_bytes", "rollout_attn_plan", "rollout_attn_decode",
     "rollout_gemm_workspace_bytes", "rollout_gemm_bf16", "rollout_stream_copy", "rollout_stream_read",
     "rollout_gemm_packed_bytes", "rollout_gemm_pack_weights", "rollout_update_weights", "rollout_submit_n",
+    "rollout_gemm_swiglu_bf16", "rollout_gemm_kernel_name", "rollout_gemm_splits",
 ]
 
 
@@ -71,7 +73,7 @@ class rollout_step_info(C.Structure):
 class rollout_traj(C.Structure):
     _fields_ = [("seq_id", C.c_uint64), ("slot", C.c_uint32), ("completion_step", C.c_uint32),
                 ("gen_len", C.c_uint32), ("group_idx", C.c_uint32), ("tok_off", C.c_uint64),
-                ("n_preempt", C.c_uint32), ("reserved", C.c_uint32)]
+                ("n_preempt", C.c_uint32), ("policy_version", C.c_uint32)]
 
 
 class rollout_stats_t(C.Structure):
@@ -112,6 +114,11 @@ lib.rollout_gemm_bf16.argtypes = [_vp, _vp, _vp, _u32, _u32, _u32, _vp, _u64, _v
 lib.rollout_gemm_packed_bytes.argtypes = [_u32, _u32]
 lib.rollout_gemm_packed_bytes.restype = _u64
 lib.rollout_gemm_pack_weights.argtypes = [_vp, _vp, _u32, _u32, _vp]
+lib.rollout_gemm_swiglu_bf16.argtypes = [_vp, _vp, _vp, _u32, _u32, _u32, _vp]
+lib.rollout_gemm_kernel_name.argtypes = [_u32, _u32, _u32, _u32, C.c_int]
+lib.rollout_gemm_splits.argtypes = [_u32, _u32, _u32]
+lib.rollout_gemm_splits.restype = _u32
+lib.rollout_gemm_kernel_name.restype = C.c_char_p
 lib.rollout_stream_copy.argtypes = [_vp, _vp, _u64, _vp]
 lib.rollout_stream_read.argtypes = [_vp, _u64, _vp, _vp]
 
@@ -296,3 +303,15 @@ def rollout_gemm_packed_bytes(N, K) -> int:
 
 def rollout_gemm_pack_weights(w_dev, packed_dev, N, K, stream=0) -> None:
     _check(lib.rollout_gemm_pack_weights(w_dev, packed_dev, N, K, stream))
+
+
+def rollout_gemm_swiglu_bf16(a_dev, w_packed_dev, act_dev, M, F, K, stream=0) -> None:
+    _check(lib.rollout_gemm_swiglu_bf16(a_dev, w_packed_dev, act_dev, M, F, K, stream))
+
+
+def rollout_gemm_kernel_name(M, N, K, splits=0, swiglu=False) -> str:
+    return lib.rollout_gemm_kernel_name(M, N, K, splits, int(bool(swiglu))).decode()
+
+
+def rollout_gemm_splits(M, N, K) -> int:
+    return lib.rollout_gemm_splits(M, N, K)

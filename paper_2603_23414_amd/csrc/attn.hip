@@ -246,38 +246,6 @@ __global__ void k_attn_merge(const int* __restrict__ row_pos, const int* __restr
   else ((uint16_t*)out)[o] = f2bf(num / den);
 }
 
-// Build the (row, chunk) work list for n_rows rows on the device: one block, any n_rows.
-__global__ __launch_bounds__(1024) void k_attn_worklist(const int* __restrict__ row_slot,
-                                                        const int* __restrict__ row_pos, int n_rows,
-                                                        int4* __restrict__ work, int* __restrict__ row_wstart,
-                                                        int* __restrict__ n_work_out, int chunk_tokens) {
-  __shared__ int scan[1024];
-  __shared__ int base;
-  if (threadIdx.x == 0) base = 0;
-  __syncthreads();
-  for (int r0 = 0; r0 < n_rows; r0 += 1024) {
-    const int r = r0 + threadIdx.x;
-    const int nch = r < n_rows ? ((row_pos[r] + 1 + chunk_tokens - 1) / chunk_tokens + ATTN_GROUP - 1) / ATTN_GROUP : 0;
-    scan[threadIdx.x] = nch;
-    __syncthreads();
-    for (int o = 1; o < 1024; o <<= 1) {
-      const int v = threadIdx.x >= o ? scan[threadIdx.x - o] : 0;
-      __syncthreads();
-      scan[threadIdx.x] += v;
-      __syncthreads();
-    }
-    const int start = base + scan[threadIdx.x] - nch;
-    if (r < n_rows) {
-      row_wstart[r] = start;
-      for (int c = 0; c < nch; ++c) work[start + c] = make_int4(r, c, row_slot[r], row_pos[r] + 1);
-    }
-    __syncthreads();
-    if (threadIdx.x == 1023) base += scan[1023];
-    __syncthreads();
-  }
-  if (threadIdx.x == 0 && n_work_out) *n_work_out = base;
-}
-
 template <int D>
 __global__ void k_write_kv(uint8_t* __restrict__ pool, int Hkv, const uint16_t* __restrict__ k,
                            const uint16_t* __restrict__ v, const int* __restrict__ tok_seq,
@@ -301,12 +269,6 @@ __global__ void k_write_kv(uint8_t* __restrict__ pool, int Hkv, const uint16_t* 
 // ---------------------------------------------------------------------------------------------------
 int attn_supported(int head_dim, int group) {
   return (head_dim == 128 && (group == 1 || group == 4 || group == 5)) || (head_dim == 32 && (group == 1 || group == 4 || group == 5));
-}
-
-void launch_attn_worklist(const int* row_slot, const int* row_pos, int n_rows, int4* work, int* row_wstart, int* n_work_out,
-                          int chunk_tokens, hipStream_t st) {
-  hipLaunchKernelGGL(k_attn_worklist, dim3(1), dim3(1024), 0, st, row_slot, row_pos, n_rows, work, row_wstart, n_work_out,
-                     chunk_tokens);
 }
 
 template <int D, int G>

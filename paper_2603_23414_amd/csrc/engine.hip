@@ -89,6 +89,12 @@ struct rollout_ctx {
   SubmitRec* sub_dev = nullptr;
   int* tok_stage_host = nullptr;
   int* tok_stage_dev = nullptr;
+  // harvest staging: records (pinned + device) and packed tokens / log-probs of one batch of trajectories
+  HarvestRec* hv_rec_host = nullptr;
+  HarvestRec* hv_rec_dev = nullptr;
+  int* hv_tok_dev = nullptr;
+  float* hv_logp_dev = nullptr;
+  size_t hv_cap = 0;
   // host bookkeeping
   std::vector<SeqHost> seqs;
   std::vector<int> free_sidx;
@@ -357,9 +363,12 @@ int run_prefill(rollout_ctx* c, int n_dec, int n_adm) {
   return 0;
 }
 
-int step_impl(rollout_ctx* c, const int32_t* forced_tok, float* logits_out, rollout_step_info* info) {
+int step_impl(rollout_ctx* c, const int32_t* forced_tok, rollout_step_info* info) {
   if (!c) return ROLLOUT_EINVAL;
   if (c->dead) return fail(c, ROLLOUT_EDEVICE, "context unusable after an earlier device error");
+  if (forced_tok)   // the emit kernel indexes the logits row and, next step, the embedding table with these
+    for (int i = 0; i < c->Q; ++i)
+      if (forced_tok[i] >= c->V) return fail(c, ROLLOUT_ERANGE, "forced token id outside the vocabulary; nothing consumed");
   const auto t0 = std::chrono::steady_clock::now();
   HIPCHK(c, hipSetDevice(c->cfg.device));
   hipStream_t st = c->stream;
@@ -417,7 +426,6 @@ int step_impl(rollout_ctx* c, const int32_t* forced_tok, float* logits_out, roll
     info->ctx_tokens = (uint64_t)(unsigned)sh[STAT_CTX_LO] | ((uint64_t)(unsigned)sh[STAT_CTX_HI] << 32);
   }
   c->wall_ms_steps += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
-  (void)logits_out;
   return 0;
 }
 
@@ -545,6 +553,7 @@ int rollout_init(rollout_ctx** out, const void* weights, size_t weights_bytes, c
   INIT_TRY(dev_alloc(c, &s.seq_completion, MS));
   INIT_TRY(dev_alloc(c, &s.seq_kv_version, MS));
   INIT_TRY(dev_alloc(c, &s.seq_npreempt, MS));
+  INIT_TRY(dev_alloc(c, &s.seq_fin_version, MS));
   INIT_TRY(dev_alloc(c, &s.seq_id, MS));
   INIT_TRY(dev_alloc(c, &s.seq_tokens, MS * s.tok_stride));
   INIT_TRY(dev_alloc(c, &s.seq_logp, MS * s.cap));
@@ -581,6 +590,11 @@ int rollout_init(rollout_ctx** out, const void* weights, size_t weights_bytes, c
   INIT_TRY(dev_alloc(c, &c->sub_dev, MS));
   INIT_TRY(host_alloc(c, &c->tok_stage_host, MS * f.max_prompt_len));
   INIT_TRY(dev_alloc(c, &c->tok_stage_dev, MS * f.max_prompt_len));
+  c->hv_cap = std::max<size_t>(f.max_new_tokens, std::min<size_t>(MS * (size_t)f.max_new_tokens, (size_t)1 << 22));
+  INIT_TRY(host_alloc(c, &c->hv_rec_host, MS));
+  INIT_TRY(dev_alloc(c, &c->hv_rec_dev, MS));
+  INIT_TRY(dev_alloc(c, &c->hv_tok_dev, c->hv_cap));
+  INIT_TRY(dev_alloc(c, &c->hv_logp_dev, c->hv_cap));
 
   // ---- activations / workspaces ----------------------------------------------------------------------
   const bool model = !(f.debug_flags & ROLLOUT_DEBUG_NO_MODEL);
@@ -711,11 +725,11 @@ int rollout_update_weights(rollout_ctx* c, const void* weights, size_t weights_b
   return r;
 }
 
-int rollout_step(rollout_ctx* c, rollout_step_info* info) { return step_impl(c, nullptr, nullptr, info); }
+int rollout_step(rollout_ctx* c, rollout_step_info* info) { return step_impl(c, nullptr, info); }
 
 int rollout_step_forced(rollout_ctx* c, const int32_t* forced_tok, float* logits_out, rollout_step_info* info) {
   if (!c) return ROLLOUT_EINVAL;
-  if (!logits_out) return step_impl(c, forced_tok, nullptr, info);
+  if (!logits_out) return step_impl(c, forced_tok, info);
   // the emit kernel rewrites the row list, so capture this step's row -> slot map before it runs:
   // the decode rows are known before the step; admitted slots come from the status block afterwards
   const int n_dec = c->status_host[STAT_NDEC_NEXT];
@@ -723,7 +737,7 @@ int rollout_step_forced(rollout_ctx* c, const int32_t* forced_tok, float* logits
   if (n_dec > 0) {
     HIPCHK(c, hipMemcpy(row_slot.data(), c->sd.row_slot, sizeof(int) * n_dec, hipMemcpyDeviceToHost));
   }
-  const int r = step_impl(c, forced_tok, logits_out, info);
+  const int r = step_impl(c, forced_tok, info);
   if (r != 0) return r;
   if (c->cfg.debug_flags & ROLLOUT_DEBUG_NO_MODEL) return 0;
   const int n_adm = c->status_host[STAT_NADM];
@@ -755,12 +769,13 @@ int rollout_harvest(rollout_ctx* c, uint32_t group_size, uint32_t flags, rollout
   }
   if (k == 0) return ROLLOUT_OK;
   const size_t MS = c->cfg.max_seqs;
-  std::vector<int> fin(nfin), comp(MS), glen(MS), slot(MS), npre(MS);
+  std::vector<int> fin(nfin), comp(MS), glen(MS), slot(MS), npre(MS), fver(MS);
   HIPCHK(c, hipMemcpy(fin.data(), c->sd.fin_list, sizeof(int) * nfin, hipMemcpyDeviceToHost));
   HIPCHK(c, hipMemcpy(comp.data(), c->sd.seq_completion, sizeof(int) * MS, hipMemcpyDeviceToHost));
   HIPCHK(c, hipMemcpy(glen.data(), c->sd.seq_gen_len, sizeof(int) * MS, hipMemcpyDeviceToHost));
   HIPCHK(c, hipMemcpy(slot.data(), c->sd.seq_slot, sizeof(int) * MS, hipMemcpyDeviceToHost));
   HIPCHK(c, hipMemcpy(npre.data(), c->sd.seq_npreempt, sizeof(int) * MS, hipMemcpyDeviceToHost));
+  HIPCHK(c, hipMemcpy(fver.data(), c->sd.seq_fin_version, sizeof(int) * MS, hipMemcpyDeviceToHost));
   // length-ordered: completion step, then generated length, then submission order
   std::sort(fin.begin(), fin.end(), [&](int a, int b) {
     if (comp[a] != comp[b]) return comp[a] < comp[b];
@@ -773,7 +788,29 @@ int rollout_harvest(rollout_ctx* c, uint32_t group_size, uint32_t flags, rollout
   if (tok_needed) *tok_needed = need_tok;
   if (!recs || (uint32_t)take > recs_cap || !tok_buf || need_tok > tok_cap)
     return fail(c, ROLLOUT_ERANGE, "output buffers too small (see n_recs / tok_needed); nothing consumed");
+  // tokens and log-probs leave the device in batches: a gather kernel packs as many trajectories as the staging
+  // buffers hold (always at least one: they hold max_new_tokens), then one copy per array moves the batch
   uint64_t off = 0;
+  for (int i0 = 0; i0 < take;) {
+    size_t fill = 0;
+    int i1 = i0;
+    while (i1 < take && fill + (size_t)glen[fin[i1]] <= c->hv_cap) {
+      const int sidx = fin[i1];
+      c->hv_rec_host[i1 - i0] = HarvestRec{sidx, c->seqs[sidx].prompt_len, glen[sidx], (int)fill};
+      fill += (size_t)glen[sidx];
+      ++i1;
+    }
+    HIPCHK(c, hipMemcpyAsync(c->hv_rec_dev, c->hv_rec_host, sizeof(HarvestRec) * (i1 - i0), hipMemcpyHostToDevice, c->stream));
+    launch_harvest_gather(c->sd, c->hv_rec_dev, i1 - i0, c->hv_tok_dev, logp_buf ? c->hv_logp_dev : nullptr, c->stream);
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    if (fill > 0) {
+      HIPCHK(c, hipMemcpy(tok_buf + off, c->hv_tok_dev, sizeof(int) * fill, hipMemcpyDeviceToHost));
+      if (logp_buf) HIPCHK(c, hipMemcpy(logp_buf + off, c->hv_logp_dev, sizeof(float) * fill, hipMemcpyDeviceToHost));
+    }
+    off += fill;
+    i0 = i1;
+  }
+  off = 0;
   for (int i = 0; i < take; ++i) {
     const int sidx = fin[i];
     rollout_traj& r = recs[i];
@@ -784,12 +821,7 @@ int rollout_harvest(rollout_ctx* c, uint32_t group_size, uint32_t flags, rollout
     r.group_idx = (uint32_t)(c->n_groups_total + (uint64_t)(i / (int)group_size));
     r.tok_off = off;
     r.n_preempt = (uint32_t)npre[sidx];
-    r.reserved = 0;
-    HIPCHK(c, hipMemcpy(tok_buf + off, c->sd.seq_tokens + (size_t)sidx * c->sd.tok_stride + c->seqs[sidx].prompt_len,
-                        sizeof(int) * glen[sidx], hipMemcpyDeviceToHost));
-    if (logp_buf)
-      HIPCHK(c, hipMemcpy(logp_buf + off, c->sd.seq_logp + (size_t)sidx * c->sd.cap, sizeof(float) * glen[sidx],
-                          hipMemcpyDeviceToHost));
+    r.policy_version = (uint32_t)fver[sidx];
     off += glen[sidx];
     c->seqs[sidx].harvested = true;
     c->seqs[sidx].in_use = false;
@@ -1039,6 +1071,26 @@ int rollout_gemm_bf16(const void* a_dev, const void* w_packed_dev, float* c_dev,
     launch_reduce_splits((const float*)workspace_dev, c_dev, (size_t)M * N, S, (hipStream_t)stream);
   }
   return hipGetLastError() == hipSuccess ? ROLLOUT_OK : fail(nullptr, ROLLOUT_EDEVICE, "kernel launch failed");
+}
+
+
+int rollout_gemm_swiglu_bf16(const void* a_dev, const void* w_packed_dev, void* act_dev, uint32_t M, uint32_t F, uint32_t K,
+                             void* stream) {
+  if (!a_dev || !w_packed_dev || !act_dev || M == 0 || F == 0 || K == 0) return fail(nullptr, ROLLOUT_EINVAL, "null argument");
+  if (K % 64 || F % 16) return fail(nullptr, ROLLOUT_EINVAL, "K must be a multiple of 64 and F of 16");
+  if (K > (1u << 20) || M > (1u << 24) || F > (1u << 23)) return fail(nullptr, ROLLOUT_EINVAL, "matrix too large");
+  launch_gemm_swiglu(a_dev, w_packed_dev, act_dev, (int)M, (int)(2 * F), (int)K, (hipStream_t)stream);
+  return hipGetLastError() == hipSuccess ? ROLLOUT_OK : fail(nullptr, ROLLOUT_EDEVICE, "kernel launch failed");
+}
+
+const char* rollout_gemm_kernel_name(uint32_t M, uint32_t N, uint32_t K, uint32_t splits, int swiglu) {
+  if (M == 0 || N == 0 || K == 0 || K % 64) return "";
+  const int S = swiglu ? 1 : splits ? (int)splits : gemm_pick_splits((int)M, (int)N, (int)K);
+  return gemm_kernel_name((int)M, (int)N, (int)K, S, swiglu ? 1 : 0);
+}
+uint32_t rollout_gemm_splits(uint32_t M, uint32_t N, uint32_t K) {
+  if (M == 0 || N == 0 || K == 0 || K % 64) return 0;
+  return (uint32_t)gemm_pick_splits((int)M, (int)N, (int)K);
 }
 
 }  // extern "C"

@@ -9,6 +9,8 @@
 // is loaded global -> LDS directly, so that the 16-byte fragment reads are bank-conflict free).  Split-K over
 // blockIdx.z writes fp32 partial sums that the consumer kernels (residual+norm, RoPE, SiLU*mul) add up in a
 // fixed order, so results are deterministic.
+#include <cstdio>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -519,46 +521,78 @@ int gemm_pick_splits(int M, int N, int K) {
   return (nkb + per - 1) / per;
 }
 
+// Which kernel a launch of M x N x K with S splits gets: every decision is taken here, once, so that a test can ask
+// (gemm_kernel_name) which instantiation a shape reaches.
+struct GemmPlan {
+  int mi;          // row-block height in units of 32 rows
+  dim3 grid;
+  int per;         // k blocks per split
+  int kind;        // 0 base kernel, 1 deep (one workgroup per CU), 2 big (several row blocks)
+  bool narrow, xmap;
+};
+static GemmPlan gemm_plan(int M, int N, int K, int S) {
+  GemmPlan p;
+  const int nkb = K / GEMM_BK;
+  p.per = (nkb + S - 1) / S;
+  p.mi = M <= 32 ? 1 : M <= 64 ? 2 : M <= 128 ? 4 : 8;
+  p.grid = dim3((N + 127) / 128, (M + 32 * p.mi - 1) / (32 * p.mi), S);
+  p.narrow = p.xmap = false;
+  p.kind = 0;
+  if (p.mi == 8 && (long long)p.grid.x * p.grid.y * p.grid.z <= 256) {   // at most one workgroup per CU: the deep variant
+    p.kind = 1;
+  } else if (p.mi == 8 && p.grid.y > 1) {   // several row blocks (prefill): 256 x 256 or 256 x 192 tiles
+    p.kind = 2;
+    // tile width: fewer rounds of 256 workgroups weighted by the width; then fewer padded columns; then the wider
+    const long long t4 = (long long)((N + 255) / 256) * p.grid.y * S, t3 = (long long)((N + 191) / 192) * p.grid.y * S;
+    const long long c4 = (t4 + 255) / 256 * 256, c3 = (t3 + 255) / 256 * 192;
+    p.narrow = c3 < c4 || (c3 == c4 && (N + 191) / 192 * 192 < (N + 255) / 256 * 256);
+    // the XCD-aware order pays with many column tiles (gate||up: 112 of them, -7 %) and costs 2-3 % with 16
+    const int gx = p.narrow ? (N + 191) / 192 : (N + 255) / 256;
+    p.xmap = gx >= 32;
+    p.grid.x = gx;
+  }
+  return p;
+}
+
+const char* gemm_kernel_name(int M, int N, int K, int S, int epi) {
+  static thread_local char buf[64];
+  const GemmPlan p = gemm_plan(M, N, K, S);
+  if (p.kind == 1) snprintf(buf, sizeof buf, "k_gemm_bf16_deep<%d>", epi);
+  else if (p.kind == 2) snprintf(buf, sizeof buf, "k_gemm_bf16_big<%d,%d,%s>", epi, p.narrow ? 3 : 4, p.xmap ? "true" : "false");
+  else snprintf(buf, sizeof buf, "k_gemm_bf16<%d,%d,true>", p.mi, epi);
+  return buf;
+}
+
 template <int EPI>
 static void launch_gemm_t(const uint16_t* a, const uint16_t* w, float* C, int M, int N, int K, int S, hipStream_t st) {
-  const int nkb = K / GEMM_BK;
-  const int per = (nkb + S - 1) / S;
-  const int mi = M <= 32 ? 1 : M <= 64 ? 2 : M <= 128 ? 4 : 8;
-  dim3 grid((N + 127) / 128, (M + 32 * mi - 1) / (32 * mi), S);
-  if (mi == 8 && (long long)grid.x * grid.y * grid.z <= 256) {   // at most one workgroup per CU: the deep variant
+  const GemmPlan p = gemm_plan(M, N, K, S);
+  const dim3 grid = p.grid;
+  const int per = p.per;
+  if (p.kind == 1) {
     hipLaunchKernelGGL((k_gemm_bf16_deep<EPI>), grid, dim3(256), 0, st, a, w, C, M, N, K, per);
     return;
   }
-  switch (mi) {   // a single row block (every decode launch) streams W; several row blocks share it through L2
-    case 1: hipLaunchKernelGGL((k_gemm_bf16<1, EPI, true>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
-    case 2: hipLaunchKernelGGL((k_gemm_bf16<2, EPI, true>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
-    case 4: hipLaunchKernelGGL((k_gemm_bf16<4, EPI, true>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
-    default:
-      if (grid.y == 1) {
-        hipLaunchKernelGGL((k_gemm_bf16<8, EPI, true>), grid, dim3(256), 0, st, a, w, C, M, N, K, per);
-      } else {   // several row blocks (prefill): 256 x 256 or 256 x 192 tiles, both operands through LDS
-        // tile width: fewer rounds of 256 workgroups weighted by the width; then fewer padded columns; then the wider
-        const long long t4 = (long long)((N + 255) / 256) * grid.y * S, t3 = (long long)((N + 191) / 192) * grid.y * S;
-        const long long c4 = (t4 + 255) / 256 * 256, c3 = (t3 + 255) / 256 * 192;
-        const bool narrow = c3 < c4 || (c3 == c4 && (N + 191) / 192 * 192 < (N + 255) / 256 * 256);
-        // the XCD-aware order pays with many column tiles (gate||up: 112 of them, -7 %) and costs 2-3 % with 16
-        const int gx = narrow ? (N + 191) / 192 : (N + 255) / 256;
-        const bool xmap = gx >= 32;
+  if (p.kind == 2) {
 #define LAUNCH_BIG(NT_, XMAP_)                                                                                          \
   {                                                                                                                     \
     static const hipError_t attr = hipFuncSetAttribute((const void*)k_gemm_bf16_big<EPI, NT_, XMAP_>,                   \
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, BIG_LDS_BYTES(NT_)); \
     (void)attr;                                                                                                         \
-    hipLaunchKernelGGL((k_gemm_bf16_big<EPI, NT_, XMAP_>), dim3(gx, grid.y, S), dim3(256), BIG_LDS_BYTES(NT_), st, a, w, C, \
-                       M, N, K, per);                                                                                   \
+    hipLaunchKernelGGL((k_gemm_bf16_big<EPI, NT_, XMAP_>), grid, dim3(256), BIG_LDS_BYTES(NT_), st, a, w, C, M, N, K,   \
+                       per);                                                                                            \
   }
-        if (narrow && xmap) LAUNCH_BIG(3, true)
-        else if (narrow) LAUNCH_BIG(3, false)
-        else if (xmap) LAUNCH_BIG(4, true)
-        else LAUNCH_BIG(4, false)
+    if (p.narrow && p.xmap) LAUNCH_BIG(3, true)
+    else if (p.narrow) LAUNCH_BIG(3, false)
+    else if (p.xmap) LAUNCH_BIG(4, true)
+    else LAUNCH_BIG(4, false)
 #undef LAUNCH_BIG
-      }
-      break;
+    return;
+  }
+  switch (p.mi) {   // a single row block (every decode launch) streams W
+    case 1: hipLaunchKernelGGL((k_gemm_bf16<1, EPI, true>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
+    case 2: hipLaunchKernelGGL((k_gemm_bf16<2, EPI, true>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
+    case 4: hipLaunchKernelGGL((k_gemm_bf16<4, EPI, true>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
+    default: hipLaunchKernelGGL((k_gemm_bf16<8, EPI, true>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
   }
 }
 

@@ -23,8 +23,6 @@ struct AttnArgs {
   int chunk_tokens;        // cached tokens per work item (multiple of 64, at most 1024)
 };
 int attn_supported(int head_dim, int group);
-void launch_attn_worklist(const int* row_slot, const int* row_pos, int n_rows, int4* work, int* row_wstart, int* n_work_out,
-                          int chunk_tokens, hipStream_t st);
 void launch_decode_attn(const AttnArgs& a, int head_dim, int group, hipStream_t st, hipEvent_t ev0 = nullptr,
                         hipEvent_t ev1 = nullptr);
 void launch_write_kv(void* pool, int Hkv, int head_dim, const void* k, const void* v, const int* tok_seq,
@@ -37,6 +35,8 @@ void launch_prefill_attn(const void* pool, const void* q, const void* tiles, int
 
 // ---- GEMM ---------------------------------------------------------------------------------------------
 int gemm_pick_splits(int M, int N, int K);
+// name of the kernel instantiation launch_gemm (epi 0) / launch_gemm_swiglu (epi 1) runs for this shape and split count
+const char* gemm_kernel_name(int M, int N, int K, int S, int epi);
 void launch_gemm(const void* A, const void* W, float* C, int M, int N, int K, int S, hipStream_t st);
 void launch_gemm_swiglu(const void* A, const void* W, void* act, int M, int N, int K, hipStream_t st);
 // row-major [N, K] -> the packed fragment layout the GEMM kernels read (N * K elements; N a multiple of 32)
@@ -80,6 +80,7 @@ struct SchedDev {
   int *slot_seq, *slot_npages, *page_table;
   int *seq_prompt_len, *seq_target_len, *seq_gen_len, *seq_state, *seq_slot, *seq_completion, *seq_kv_version,
       *seq_npreempt;
+  int* seq_fin_version;    // policy version under which the rollout's last token was produced (set when it finishes)
   unsigned long long* seq_id;
   int* seq_tokens;
   float* seq_logp;
@@ -105,6 +106,11 @@ void launch_sched_emit(const SchedDev& d, hipStream_t st);
 void launch_sched_boundary(const SchedDev& d, int n_groups, hipStream_t st);
 void launch_sched_submit(const SchedDev& d, const SubmitRec* recs, const int* tok_staging, int n, hipStream_t st);
 void launch_sched_init(const SchedDev& d, hipStream_t st);
+
+// harvest: one finished rollout whose gen_len tokens (and log-probs) go to offset `off` of the staging buffers
+struct HarvestRec { int sidx, prompt_len, gen_len, off; };
+void launch_harvest_gather(const SchedDev& d, const HarvestRec* recs, int n, int* tok_out, float* logp_out,
+                           hipStream_t st);
 
 // prefill planning: token rows of the admitted sequences
 struct PrefillDesc { int slot, sidx, n_tok, pos_begin, row_begin; };   // a run of consecutive positions of one sequence

@@ -263,6 +263,7 @@ __global__ __launch_bounds__(1024) void k_sched_emit(SchedDev d) {
   if (fin) {
     d.fin_list[fin0 + fin_rank] = my_sidx;
     d.seq_completion[my_sidx] = step;
+    d.seq_fin_version[my_sidx] = d.sc[SC_VERSION];
     d.seq_state[my_sidx] = SEQ_FINISHED;
   }
   release_flagged(d, sh, grp_of, fin != 0);
@@ -415,6 +416,7 @@ __global__ __launch_bounds__(256) void k_sched_submit_copy(SchedDev d, const Sub
     d.seq_slot[r.sidx] = -1;
     d.seq_completion[r.sidx] = -1;
     d.seq_kv_version[r.sidx] = 0;
+    d.seq_fin_version[r.sidx] = 0;
     d.seq_npreempt[r.sidx] = 0;
     d.seq_id[r.sidx] = r.seq_id;
     d.seq_group[r.sidx] = r.group;
@@ -461,6 +463,23 @@ __global__ __launch_bounds__(256) void k_prefill_rows(SchedDev d, const PrefillD
     row_pos[row] = p.pos_begin + i;
     row_tok[row] = d.seq_tokens[(size_t)p.sidx * d.tok_stride + p.pos_begin + i];
   }
+}
+
+// Harvest: pack the generated tokens and log-probs of a batch of finished rollouts into contiguous staging buffers
+// (one workgroup per rollout), so that the host needs one copy per array instead of two per trajectory.
+__global__ __launch_bounds__(256) void k_harvest_gather(SchedDev d, const HarvestRec* __restrict__ recs,
+                                                        int* __restrict__ tok_out, float* __restrict__ logp_out) {
+  const HarvestRec r = recs[blockIdx.x];
+  const int* src = d.seq_tokens + (size_t)r.sidx * d.tok_stride + r.prompt_len;
+  const float* lsrc = d.seq_logp + (size_t)r.sidx * d.cap;
+  for (int i = threadIdx.x; i < r.gen_len; i += 256) {
+    tok_out[r.off + i] = src[i];
+    if (logp_out) logp_out[r.off + i] = lsrc[i];
+  }
+}
+void launch_harvest_gather(const SchedDev& d, const HarvestRec* recs, int n, int* tok_out, float* logp_out,
+                           hipStream_t st) {
+  if (n > 0) hipLaunchKernelGGL(k_harvest_gather, dim3(n), dim3(256), 0, st, d, recs, tok_out, logp_out);
 }
 
 void launch_sched_admit(const SchedDev& d, hipStream_t st) { hipLaunchKernelGGL(k_sched_admit, dim3(1), dim3(1024), 0, st, d); }

@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 import workloads as W
-from tests._util import flat_prompts, make_engine, make_oracle
+from tests._util import LogitError, flat_prompts, lockstep_teacher_forced, make_engine, make_oracle
 
 pytestmark = pytest.mark.gpu
 
@@ -82,12 +82,12 @@ def test_scheduler_bit_exact_at_full_scale(name):
                         io["free_pages"], len(io["admitted"]), len(io["finished"]))
             if len(orc.finished) >= c.harvest:
                 ng, recs, tk, lp = R.rollout_harvest(ctx, c.harvest, 0, want_logp=False)
-                got += [(r.seq_id, r.slot, r.completion_step, r.gen_len, r.group_idx) for r in recs]
-                ref += [(s.seq_id, s.last_slot, s.completion_step, s.gen_len, s.group_idx)
+                got += [(r.seq_id, r.slot, r.completion_step, r.gen_len, r.group_idx, r.policy_version) for r in recs]
+                ref += [(s.seq_id, s.last_slot, s.completion_step, s.gen_len, s.group_idx, s.policy_version)
                         for g in orc.harvest(c.harvest) for s in g]
         ng, recs, tk, lp = R.rollout_harvest(ctx, c.harvest, R.ROLLOUT_FLUSH, want_logp=False)
-        got += [(r.seq_id, r.slot, r.completion_step, r.gen_len, r.group_idx) for r in recs]
-        ref += [(s.seq_id, s.last_slot, s.completion_step, s.gen_len, s.group_idx)
+        got += [(r.seq_id, r.slot, r.completion_step, r.gen_len, r.group_idx, r.policy_version) for r in recs]
+        ref += [(s.seq_id, s.last_slot, s.completion_step, s.gen_len, s.group_idx, s.policy_version)
                 for g in orc.harvest(c.harvest, flush=True) for s in g]
         assert got == ref and len(got) == c.n_prompts
         st, so = R.rollout_stats(ctx), orc.stats()
@@ -98,43 +98,27 @@ def test_scheduler_bit_exact_at_full_scale(name):
         R.rollout_destroy(ctx)
 
 
-@pytest.mark.parametrize("name", ["8b", "32b"])
-def test_one_layer_slice_at_full_widths_teacher_forced(name):
-    """One layer of the real widths (d_model, heads, FFN, full vocabulary): a few rollouts with 17-70 token prompts
-    under teacher forcing.  The 2e-2 gate is stated for the smallest config, whose logits have standard deviation
-    0.02 * sqrt(128); bf16 rounding of the GEMM inputs gives an error proportional to the logit scale, so at width D
-    the same relative bar is 2e-2 * sqrt(D / 128) (0.113 at 4096, 0.126 at 5120)."""
+@pytest.mark.parametrize("name,layers", [("8b", 1), ("32b", 1), ("8b", 2), ("32b", 2)])
+def test_slices_at_full_widths_teacher_forced(name, layers):
+    """One and two layers of the real widths (d_model, heads, FFN, full vocabulary): a few rollouts with 17-70 token
+    prompts under teacher forcing.  The bar is the one of the 128-wide parity gate carried over by the logit scale
+    (LOGIT_REL_TOL of the oracle logits' standard deviation); the absolute and the relative error are printed per
+    depth."""
     import paper_2603_23414_amd as R
-    from tests._util import info_tuple
-    m = W.CONFIGS[name].model.with_layers(1)
+    m = W.CONFIGS[name].model.with_layers(layers)
     blob = W.make_weights(m, 5)
     g = W.rng(6)
-    prompts = [g.integers(0, m.vocab - 1, int(k)).astype(np.int32) for k in (40, 70, 17)]
-    L = np.array([3, 2, 4], np.uint32)
+    prompts = [g.integers(0, m.vocab - 1, int(k)).astype(np.int32) for k in ((40, 70, 17) if layers == 1 else (21, 9))]
+    L = np.array([3, 2, 4] if layers == 1 else [2, 3], np.uint32)
     orc = make_oracle(m, max_slots=2, max_prompt_len=70, cap=8, weights_blob=blob, dtype=np.float32)
-    ctx = make_engine(m, blob, max_slots=2, max_prompt_len=70, cap=8, max_seqs=3)
+    ctx = make_engine(m, blob, max_slots=2, max_prompt_len=70, cap=8, max_seqs=len(prompts))
     try:
         toks, offs = flat_prompts(prompts)
         R.rollout_submit(ctx, toks, offs, L)
         orc.submit(prompts, L)
-        logits = np.zeros((2, m.vocab), np.float32)
-        worst, rows = 0.0, 0
-        while orc.queue or any(x is not None for x in orc.slots):
-            before = [s.gen_len for s in orc.seqs]
-            io = orc.step()
-            forced = np.full(2, -1, np.int32)
-            ran = {}
-            for s in orc.seqs:
-                if s.gen_len > before[s.seq_id]:
-                    forced[s.last_slot] = s.tokens[-1]
-                    ran[s.last_slot] = s
-            ig = R.rollout_step_forced(ctx, forced, logits)
-            assert info_tuple(ig) == info_tuple(io)
-            for slot in ran:
-                worst = max(worst, float(np.max(np.abs(logits[slot] - orc.last_logits[slot]))))
-                rows += 1
-        assert rows == int(L.sum())
-        assert worst < 2e-2 * np.sqrt(m.d_model / 128.0), worst
-        print(f"{name}: worst |logit error| {worst:.4f} over {rows} rows")
+        err = LogitError(0.02 * np.sqrt(m.d_model))
+        lockstep_teacher_forced(R, ctx, orc, 2, m.vocab, 2, err)
+        assert err.rows == int(L.sum())
+        err.check(f"{name} widths, {layers} layer(s)")
     finally:
         R.rollout_destroy(ctx)

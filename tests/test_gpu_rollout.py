@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 
 import workloads as W
-from tests._util import flat_prompts, info_tuple, make_engine, make_oracle
+from tests._util import LOGIT_REL_TOL, LogitError, flat_prompts, info_tuple, make_engine, make_oracle
 
 pytestmark = pytest.mark.gpu
 
@@ -15,8 +15,8 @@ def _harvest_both(R, ctx, orc, G, flush=False):
     flat = [s for g in groups for s in g]
     assert len(recs) == len(flat)
     for r, s in zip(recs, flat):
-        assert (r.seq_id, r.slot, r.completion_step, r.gen_len, r.group_idx, r.n_preempt) == \
-               (s.seq_id, s.last_slot, s.completion_step, s.gen_len, s.group_idx, s.n_preempt)
+        assert (r.seq_id, r.slot, r.completion_step, r.gen_len, r.group_idx, r.n_preempt, r.policy_version) == \
+               (s.seq_id, s.last_slot, s.completion_step, s.gen_len, s.group_idx, s.n_preempt, s.policy_version)
     return recs, toks, logp, flat
 
 
@@ -95,9 +95,11 @@ def test_scheduler_hand_built_preemption_case():
 
 
 def _teacher_forced(m, blob, prompts, L, *, Q, cap, G, max_prompt_len=None, kv_pool_pages=0, max_staleness=-1,
-                    tol=2e-2, seed_pages=0, swap_blob=None):
+                    abs_tol=None, seed_pages=0, swap_blob=None, w_std=0.02):
     """Run oracle (with the model) and engine in lockstep; the engine is fed the oracle's token at every step and
-    its fp32 logits rows are compared.  Returns (worst |logit error|, rows compared, argmax agreement)."""
+    its fp32 logits rows are compared.  The bar is the same on every shape: worst error below LOGIT_REL_TOL times
+    the standard deviation of the oracle's logits (which is 2e-2 absolute on the 128-wide parity config; abs_tol
+    additionally asserts an absolute bound).  Returns (worst |logit error|, rows compared, argmax agreement)."""
     import paper_2603_23414_amd as R
     P = max_prompt_len or max(len(p) for p in prompts)
     page_bytes = m.n_layers * m.n_kv_heads * 2 * 16 * m.head_dim * 2
@@ -111,7 +113,8 @@ def _teacher_forced(m, blob, prompts, L, *, Q, cap, G, max_prompt_len=None, kv_p
         R.rollout_submit(ctx, toks, offs, L)
         orc.submit(prompts, L)
         logits = np.zeros((Q, m.vocab), np.float32)
-        worst, rows, agree, harvested = 0.0, 0, 0, []
+        err = LogitError(w_std * np.sqrt(m.d_model))
+        agree, harvested = 0, []
         while orc.queue or any(x is not None for x in orc.slots):
             before = [s.gen_len for s in orc.seqs]
             io = orc.step()
@@ -127,9 +130,7 @@ def _teacher_forced(m, blob, prompts, L, *, Q, cap, G, max_prompt_len=None, kv_p
             assert len(ran) == io["r"]
             for slot, s in ran.items():
                 ref = orc.last_logits[slot]
-                err = float(np.max(np.abs(logits[slot].astype(np.float64) - ref)))
-                worst = max(worst, err)
-                rows += 1
+                err.add(logits[slot], ref)
                 agree += int(np.argmax(logits[slot]) == int(np.argmax(ref)))
             if len(orc.finished) >= G:
                 recs, tk, lp, flat = _harvest_both(R, ctx, orc, G)
@@ -143,13 +144,14 @@ def _teacher_forced(m, blob, prompts, L, *, Q, cap, G, max_prompt_len=None, kv_p
         recs, tk, lp, flat = _harvest_both(R, ctx, orc, G, flush=True)
         harvested += [(r, tk, lp, s) for r, s in zip(recs, flat)]
         assert len(harvested) == len(prompts)
+        err.check(f"D={m.d_model} L={m.n_layers} V={m.vocab}", abs_tol)
         for r, tk, lp, s in harvested:
             assert list(tk[r.tok_off:r.tok_off + r.gen_len]) == s.tokens
-            assert np.max(np.abs(lp[r.tok_off:r.tok_off + r.gen_len] - np.array(s.logp))) < tol + 1e-2
+            # |d log-prob| <= |d logit of the token| + |d log-sum-exp| <= twice the logits bar
+            assert np.max(np.abs(lp[r.tok_off:r.tok_off + r.gen_len] - np.array(s.logp))) < 2 * LOGIT_REL_TOL * err.sigma
             assert np.all(lp[r.tok_off:r.tok_off + r.gen_len] <= 1e-6)
         _compare_stats(R, ctx, orc)
-        assert worst < tol, worst
-        return worst, rows, agree
+        return err.worst, err.rows, agree
     finally:
         R.rollout_destroy(ctx)
 
@@ -162,7 +164,7 @@ def test_tiny_policy_teacher_forced_logits_and_scheduler():
     blob = W.make_weights(m, c.seed_weights)
     prompts = list(W.make_prompts(c.n_prompts, c.prompt_len, m.vocab, c.seed_prompts))
     L = W.make_target_lengths(c.n_prompts, c.len_mu, c.len_sigma, c.cap, c.seed_lengths)
-    worst, rows, agree = _teacher_forced(m, blob, prompts, L, Q=c.max_slots, cap=c.cap, G=c.harvest)
+    worst, rows, agree = _teacher_forced(m, blob, prompts, L, Q=c.max_slots, cap=c.cap, G=c.harvest, abs_tol=2e-2)
     assert rows == int(L.sum())
     assert agree >= 0.98 * rows
 
@@ -317,6 +319,9 @@ def test_error_paths():
         assert e.value.code == -3
         assert R.rollout_harvest(ctx, 2)[0] == 0
         R.rollout_submit(ctx, np.zeros(3, np.int32), [0, 3], [2])
+        with pytest.raises(R.RolloutError) as e:                 # a forced token outside the vocabulary: refused whole
+            R.rollout_step_forced(ctx, np.array([m.vocab, -1, -1, -1], np.int32), None)
+        assert e.value.code == -4 and R.rollout_stats(ctx).steps == 0
         R.rollout_step(ctx)
         tk, lp, state, slot = R.rollout_peek(ctx, 0, 32)
         assert len(tk) == 1 and state == 1 and slot == 0
