@@ -88,6 +88,13 @@ typedef struct rollout_step_info {
   uint32_t n_preempted_step;
   uint64_t ctx_tokens;             /* cached tokens over the running requests after the step: what the next step's
                                       decode attention reads (times the per-token KV bytes) */
+  /* the work this step did (Sec. 2.2: a step streams the weights once, the KV caches of its decode rows, and computes
+   * the prefill of the slots it refilled) */
+  uint32_t n_decode_rows;          /* rows that decoded one token on top of their cache (n_ran - n_admitted) */
+  uint32_t prefill_tokens;         /* token positions prefilled for the slots admitted this step */
+  uint64_t decode_ctx_tokens;      /* cached tokens the decode rows attended over, per layer */
+  uint64_t prefill_ctx_pairs;      /* sum over the prefilled positions of their causal context length (query-key pairs
+                                      of the prefill attention, per layer and head) */
 } rollout_step_info;
 
 typedef struct rollout_traj {

@@ -67,7 +67,10 @@ class rollout_cfg(C.Structure):
 class rollout_step_info(C.Structure):
     _fields_ = [("step", C.c_uint64)] + [(n, C.c_uint32) for n in
                 ("n_ran", "n_active", "n_finished_unharvested", "n_queued", "free_pages", "n_admitted",
-                 "n_finished_step", "n_preempted_step")] + [("ctx_tokens", C.c_uint64)]
+                 "n_finished_step", "n_preempted_step")] + [("ctx_tokens", C.c_uint64), ("n_decode_rows", C.c_uint32),
+                                                            ("prefill_tokens", C.c_uint32),
+                                                            ("decode_ctx_tokens", C.c_uint64),
+                                                            ("prefill_ctx_pairs", C.c_uint64)]
 
 
 class rollout_traj(C.Structure):
@@ -315,3 +318,4 @@ def rollout_gemm_kernel_name(M, N, K, splits=0, swiglu=False) -> str:
 
 def rollout_gemm_splits(M, N, K) -> int:
     return lib.rollout_gemm_splits(M, N, K)
+

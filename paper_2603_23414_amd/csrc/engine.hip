@@ -378,11 +378,17 @@ int step_impl(rollout_ctx* c, const int32_t* forced_tok, rollout_step_info* info
   const unsigned long long ctx_sum = (unsigned long long)(unsigned)sh[STAT_CTX_LO] | ((unsigned long long)(unsigned)sh[STAT_CTX_HI] << 32);
   const int n_active = sh[STAT_NACTIVE];
   int n_adm = 0;
+  unsigned long long pf_tokens = 0, pf_pairs = 0;
   const bool can_admit = sh[STAT_QUEUED] > 0 && n_active < Q && !(c->cfg.mode == ROLLOUT_MODE_SYNC && n_active > 0);
   if (can_admit) {
     launch_sched_admit(c->sd, st);
     TRY(sync_status(c));
     n_adm = sh[STAT_NADM];
+    for (int a = 0; a < n_adm; ++a) {   // positions first .. n-1 of each admitted rollout are computed; position p sees p+1 keys
+      const unsigned long long n = (unsigned)sh[STAT_HDR + STAT_ADM_INTS * a + 2], first = (unsigned)sh[STAT_HDR + STAT_ADM_INTS * a + 3];
+      pf_tokens += n - first;
+      pf_pairs += (n * (n + 1) - first * (first + 1)) / 2;
+    }
   }
   if (forced_tok) {
     HIPCHK(c, hipMemcpyAsync(c->forced_tok_dev, forced_tok, sizeof(int) * Q, hipMemcpyHostToDevice, st));
@@ -424,6 +430,10 @@ int step_impl(rollout_ctx* c, const int32_t* forced_tok, rollout_step_info* info
     info->n_finished_step = (uint32_t)sh[STAT_NFIN_STEP];
     info->n_preempted_step = (uint32_t)sh[STAT_NPRE_STEP];
     info->ctx_tokens = (uint64_t)(unsigned)sh[STAT_CTX_LO] | ((uint64_t)(unsigned)sh[STAT_CTX_HI] << 32);
+    info->n_decode_rows = (uint32_t)n_dec;
+    info->prefill_tokens = (uint32_t)pf_tokens;
+    info->decode_ctx_tokens = n_dec > 0 ? ctx_sum : 0;
+    info->prefill_ctx_pairs = pf_pairs;
   }
   c->wall_ms_steps += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
   return 0;

@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_layouts_match_the_header():
     import paper_2603_23414_amd as R
     assert ctypes.sizeof(R.rollout_cfg) == 136 and ctypes.sizeof(R.rollout_traj) == 40
-    assert ctypes.sizeof(R.rollout_step_info) == 48 and ctypes.sizeof(R.rollout_stats_t) == 136
+    assert ctypes.sizeof(R.rollout_step_info) == 72 and ctypes.sizeof(R.rollout_stats_t) == 136
     assert R.rollout_cfg.kv_pool_bytes.offset == 56 and R.rollout_cfg.page_seed.offset == 104
 
 

@@ -44,10 +44,24 @@ def _scheduler_only(L, *, Q, P, cap, G, kv_pool_pages=0, max_staleness=-1, mode=
         assert R.rollout_submit(ctx, toks, offs, L) == orc.submit(prompts, L)
         harvested = 0
         while orc.queue or any(x is not None for x in orc.slots):
+            before = [s.gen_len for s in orc.seqs]
+            pf_before = orc.prefill_tokens
             io = orc.step()
             ig = R.rollout_step(ctx)
             assert info_tuple(ig) == info_tuple(io), (info_tuple(ig), info_tuple(io))
             assert ig.ctx_tokens == sum(len(s.prompt) + s.gen_len for s in orc.slots if s is not None)
+            # the step's own work record: decode rows and the context they attended, prefilled positions and their
+            # causal query-key pairs
+            adm = {sid for sid, _ in io["admitted"]}
+            ran = [s for s in orc.seqs if s.gen_len > before[s.seq_id]]
+            dec = [s for s in ran if s.seq_id not in adm]
+            pairs = 0
+            for s in ran:
+                if s.seq_id in adm:
+                    n_tok, p0 = len(s.prompt) + s.gen_len - 1, s.prefill_from
+                    pairs += (n_tok * (n_tok + 1) - p0 * (p0 + 1)) // 2
+            assert (ig.n_decode_rows, ig.decode_ctx_tokens, ig.prefill_tokens, ig.prefill_ctx_pairs) == \
+                   (len(dec), sum(len(s.prompt) + s.gen_len - 1 for s in dec), orc.prefill_tokens - pf_before, pairs)
             for slot in range(0, Q, max(1, Q // 4)):                  # sampled page tables
                 s = orc.slots[slot]
                 pages = R.rollout_slot_pages(ctx, slot, 4096)
