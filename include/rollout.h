@@ -246,6 +246,20 @@ uint64_t rollout_gemm_workspace_bytes(uint32_t M, uint32_t N, uint32_t K);
 int rollout_gemm_bf16(const void* a_dev, const void* w_packed_dev, float* c_dev, uint32_t M, uint32_t N, uint32_t K,
                       void* workspace_dev, uint64_t workspace_bytes, void* stream);
 
+/* rollout_gemm_bf16 for callers that cannot allocate device memory or pass a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments without the workspace, same kernels,
+ * same result bit for bit.  The split-K partial sums go to a fixed array of rollout_gemm_static_scratch_bytes()
+ * (32 MiB) inside the library's device image; every GPU the library runs on holds its own copy until the process
+ * ends.  The call runs on the current device, allocates nothing (no hipMalloc / hipFree, no allocating library
+ * routine) and only enqueues on `stream`.  Errors: EINVAL as rollout_gemm_bf16; ERANGE when
+ * rollout_gemm_splits(M, N, K) * M * N * 4 bytes exceed the array (shapes with one split need no scratch and are never
+ * refused: all decode projections of the 8B and 32B shapes at their batch sizes fit); EDEVICE.  All calls on one GPU
+ * share that GPU's array, which keeps the last call's contents (every split overwrites its whole partial, nothing
+ * needs clearing): calls that overlap on one GPU -- different streams or threads -- race, so serialise them. */
+uint64_t rollout_gemm_static_scratch_bytes(void);
+int rollout_gemm_bf16_static(const void* a_dev, const void* w_packed_dev, float* c_dev, uint32_t M, uint32_t N, uint32_t K,
+                             void* stream);
+
 /* The gate/up projection with its SwiGLU epilogue alone (the largest weight stream of a decode step, Sec. 2.2):
  * act[M, F] (bf16) = silu(a Wg^T) * (a Wu^T), a bf16 [M, K].  w_packed_dev is rollout_gemm_pack_weights applied to the
  * [2F, K] matrix whose rows interleave gate and up in blocks of 16: rows 32q .. 32q+15 = Wg rows 16q .. 16q+15,

@@ -18,7 +18,7 @@ __all__ = [
     "rollout_attn_decode", "rollout_gemm_workspace_bytes", "rollout_gemm_bf16", "rollout_stream_copy",
     "rollout_stream_read", "rollout_gemm_packed_bytes", "rollout_gemm_pack_weights", "rollout_update_weights",
     "rollout_submit_n", "rollout_gemm_swiglu_bf16", "rollout_gemm_kernel_name", "rollout_gemm_splits",
-    "make_cfg",
+    "rollout_gemm_bf16_static", "rollout_gemm_static_scratch_bytes", "make_cfg",
     "ROLLOUT_FLUSH", "ROLLOUT_DEBUG_NO_MODEL", "ROLLOUT_DEBUG_TIME_ATTN", "ROLLOUT_MODE_PARTIAL",
     "ROLLOUT_MODE_ONPOLICY", "ROLLOUT_MODE_SYNC", "ROLLOUT_EOS_FORCED_ONLY", "ROLLOUT_EOS_NATURAL_OR_FORCED",
     "EXPORTS",
@@ -42,7 +42,8 @@ EXPORTS = [
     "rollout_attn_write_kv", "rollout_attn_workspace_bytes", "rollout_attn_plan", "rollout_attn_decode",
     "rollout_gemm_workspace_bytes", "rollout_gemm_bf16", "rollout_stream_copy", "rollout_stream_read",
     "rollout_gemm_packed_bytes", "rollout_gemm_pack_weights", "rollout_update_weights", "rollout_submit_n",
-    "rollout_gemm_swiglu_bf16", "rollout_gemm_kernel_name", "rollout_gemm_splits",
+    "rollout_gemm_swiglu_bf16", "rollout_gemm_kernel_name", "rollout_gemm_splits", "rollout_gemm_bf16_static",
+    "rollout_gemm_static_scratch_bytes",
 ]
 
 
@@ -117,6 +118,9 @@ lib.rollout_gemm_bf16.argtypes = [_vp, _vp, _vp, _u32, _u32, _u32, _vp, _u64, _v
 lib.rollout_gemm_packed_bytes.argtypes = [_u32, _u32]
 lib.rollout_gemm_packed_bytes.restype = _u64
 lib.rollout_gemm_pack_weights.argtypes = [_vp, _vp, _u32, _u32, _vp]
+lib.rollout_gemm_bf16_static.argtypes = [_vp, _vp, _vp, _u32, _u32, _u32, _vp]
+lib.rollout_gemm_static_scratch_bytes.argtypes = []
+lib.rollout_gemm_static_scratch_bytes.restype = _u64
 lib.rollout_gemm_swiglu_bf16.argtypes = [_vp, _vp, _vp, _u32, _u32, _u32, _vp]
 lib.rollout_gemm_kernel_name.argtypes = [_u32, _u32, _u32, _u32, C.c_int]
 lib.rollout_gemm_splits.argtypes = [_u32, _u32, _u32]
@@ -319,3 +323,10 @@ def rollout_gemm_kernel_name(M, N, K, splits=0, swiglu=False) -> str:
 def rollout_gemm_splits(M, N, K) -> int:
     return lib.rollout_gemm_splits(M, N, K)
 
+
+def rollout_gemm_bf16_static(a_dev, w_dev, c_dev, M, N, K, stream=0) -> None:
+    _check(lib.rollout_gemm_bf16_static(a_dev, w_dev, c_dev, M, N, K, stream))
+
+
+def rollout_gemm_static_scratch_bytes() -> int:
+    return lib.rollout_gemm_static_scratch_bytes()

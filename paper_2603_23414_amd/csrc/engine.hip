@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <unordered_map>
 #include <vector>
@@ -16,6 +17,11 @@
 #include "kernels.h"
 
 #define PF_ROWS 4096          // token rows per prefill pass
+
+// Scratch of rollout_gemm_bf16_static (split-K partial sums for callers that cannot allocate).  The name is a host-side
+// stand-in: host code only ever uses the per-device address static_scratch() looks up.
+#define GEMM_STATIC_SCRATCH_BYTES (32ull << 20)
+static __device__ __align__(256) unsigned char scratch[GEMM_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -436,6 +442,30 @@ int step_impl(rollout_ctx* c, const int32_t* forced_tok, rollout_step_info* info
     info->prefill_ctx_pairs = pf_pairs;
   }
   c->wall_ms_steps += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+  return 0;
+}
+
+// ---- the projection GEMM for callers that cannot allocate ---------------------------------------------------
+// Split-K partial sums live in a fixed array inside the library's device image instead of a caller workspace.  Each
+// GPU holds its own copy of the array at its own address: the address is looked up once per device, with that device
+// current, and only that pointer is ever handed to kernels (the array's name is a host-side stand-in, not a device
+// address).
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+    return fail(nullptr, ROLLOUT_EDEVICE, "no current HIP device (or its ordinal is above 63)");
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p)
+      return fail(nullptr, ROLLOUT_EDEVICE, std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e));
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
   return 0;
 }
 
@@ -1083,6 +1113,33 @@ int rollout_gemm_bf16(const void* a_dev, const void* w_packed_dev, float* c_dev,
   return hipGetLastError() == hipSuccess ? ROLLOUT_OK : fail(nullptr, ROLLOUT_EDEVICE, "kernel launch failed");
 }
 
+
+// ---- the projection GEMM for callers that cannot allocate (static scratch: see static_scratch above) ----------
+uint64_t rollout_gemm_static_scratch_bytes(void) { return GEMM_STATIC_SCRATCH_BYTES; }
+
+int rollout_gemm_bf16_static(const void* a_dev, const void* w_packed_dev, float* c_dev, uint32_t M, uint32_t N, uint32_t K,
+                             void* stream) {
+  if (!a_dev || !w_packed_dev || !c_dev || M == 0 || N == 0 || K == 0) return fail(nullptr, ROLLOUT_EINVAL, "null argument");
+  if (K % 64) return fail(nullptr, ROLLOUT_EINVAL, "K must be a multiple of 64");
+  if (K > (1u << 20) || M > (1u << 24) || N > (1u << 24))
+    return fail(nullptr, ROLLOUT_EINVAL, "matrix too large (K <= 2^20, M and N <= 2^24)");
+  const int S = gemm_pick_splits((int)M, (int)N, (int)K);
+  if (S == 1) {
+    launch_gemm(a_dev, w_packed_dev, c_dev, (int)M, (int)N, (int)K, 1, (hipStream_t)stream);
+  } else {
+    const uint64_t need = (uint64_t)S * M * N * 4ull;
+    if (need > GEMM_STATIC_SCRATCH_BYTES)
+      return fail(nullptr, ROLLOUT_ERANGE,
+                  "split-K partial sums of this shape (" + std::to_string(need) + " bytes) exceed the library's static scratch (" +
+                      std::to_string(GEMM_STATIC_SCRATCH_BYTES) + " bytes): use rollout_gemm_bf16 with a workspace");
+    void* part = nullptr;
+    TRY(static_scratch(&part));
+    // every split writes all M x N of its partial sums, so nothing has to start at zero
+    launch_gemm(a_dev, w_packed_dev, (float*)part, (int)M, (int)N, (int)K, S, (hipStream_t)stream);
+    launch_reduce_splits((const float*)part, c_dev, (size_t)M * N, S, (hipStream_t)stream);
+  }
+  return hipGetLastError() == hipSuccess ? ROLLOUT_OK : fail(nullptr, ROLLOUT_EDEVICE, "kernel launch failed");
+}
 
 int rollout_gemm_swiglu_bf16(const void* a_dev, const void* w_packed_dev, void* act_dev, uint32_t M, uint32_t F, uint32_t K,
                              void* stream) {
