@@ -222,7 +222,10 @@ uint64_t rollout_attn_workspace_bytes(uint32_t n, uint64_t total_ctx, uint32_t n
  * (one workgroup per kv head) per four consecutive chunks of a sequence.  The chunk (cached tokens per wavefront, a
  * multiple of 64 in 128..1024) is chosen from the total context so that the wavefronts make about five rounds over
  * the chip; it is returned in chunk_tokens and must be passed to rollout_attn_decode; n_work receives the number
- * of items.  Synchronous (blocking host-to-device copies). */
+ * of items.  Also zeroes the per-(sequence, kv head) arrival counters with which the work items of a long sequence
+ * find out which of them finishes last and merges their partial results; every rollout_attn_decode leaves them at
+ * zero again, so one plan serves any number of launches -- but launches that overlap in time must not share a
+ * workspace.  Synchronous (blocking host-to-device copies). */
 int rollout_attn_plan(const int32_t* ctx_len, uint32_t n, uint32_t n_q_heads, uint32_t n_kv_heads, uint32_t head_dim,
                       void* workspace_dev, uint64_t workspace_bytes, uint32_t* n_work, uint32_t* chunk_tokens);
 

@@ -17,14 +17,32 @@
 #include "kernels.h"
 
 #define ATTN_GROUP ATTN_GROUP_CHUNKS   // chunks per workgroup
+// Workgroup id -> (work item, kv head).  With the kv head as the fastest-varying grid dimension, consecutive
+// workgroup ids (which the dispatcher deals round-robin to the 8 XCDs) are the kv heads of one work item, so all the
+// chunk groups of one (row, kv head) run on the same XCD and their partial results meet in one L2.
+#ifndef ATTN_KVH_FASTEST
+#define ATTN_KVH_FASTEST 1
+#endif
 
 #define NEG_BIG (-1.0e30f)
 
+// Partial results travel between workgroups that may sit on different XCDs (each with its own L2): they are written and
+// read with agent-scope accesses, which go through to the memory side instead of staying in the writer's L2.  That is
+// all the coherence the exchange needs; an agent-scope FENCE would also write back / invalidate the whole L2 of the XCD
+// and costs three times the kernel (measured: 1.5-1.9 ms against 0.48 ms).
+__device__ __forceinline__ void st_agent(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_agent(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 template <int D, int G>
-__global__ __launch_bounds__(256) void k_decode_attn(
+__global__ __launch_bounds__(64 * ATTN_GROUP) void k_decode_attn(
     const uint8_t* __restrict__ pool, const uint16_t* __restrict__ q, const int* __restrict__ page_table, int max_pages,
-    const int4* __restrict__ work, int Hkv, float* __restrict__ part_acc, float* __restrict__ part_ml,
-    void* __restrict__ out, int out_fp32, float scale_log2e, int chunk_tokens) {
+    const int4* __restrict__ work, const int2* __restrict__ row_wstart, int Hkv, float* __restrict__ part_acc,
+    float* __restrict__ part_ml, int* __restrict__ row_cnt, void* __restrict__ out, int out_fp32, float scale_log2e,
+    int chunk_tokens) {
   constexpr int NCH = D / 8;
   constexpr int DPL = (D + 63) / 64;
   constexpr int KBYTES = PAGE_TOKENS * D * 2;
@@ -32,11 +50,16 @@ __global__ __launch_bounds__(256) void k_decode_attn(
   __shared__ __align__(16) uint16_t p_lds[ATTN_GROUP][G][64];
   __shared__ float acc_s[ATTN_GROUP][G][DPL * 64];
   __shared__ float ml_s[ATTN_GROUP][G][2];
+  __shared__ int last_s;
 
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: keeps q addressing scalar
-  const int kvh = blockIdx.y;
-  const int4 it = work[blockIdx.x];               // one load, then page ids and query go out together
+#if ATTN_KVH_FASTEST
+  const int kvh = blockIdx.x, wi = blockIdx.y;
+#else
+  const int kvh = blockIdx.y, wi = blockIdx.x;
+#endif
+  const int4 it = work[wi];                       // one load, then page ids and query go out together
   const int row = it.x, group = it.y, slot = it.z, ctx = it.w;
   // the group's token range is cut evenly (in 64-token tiles) over the four wavefronts, so they finish together; a
   // wavefront left without tokens contributes weight zero to the merge
@@ -191,59 +214,62 @@ __global__ __launch_bounds__(256) void k_decode_attn(
         }
       }
     } else {
-      const size_t pi = (size_t)blockIdx.x * Hq + head;
+      const size_t pi = (size_t)wi * Hq + head;
 #pragma unroll
       for (int dd = 0; dd < DPL; ++dd) {
         const int dim = lane + dd * 64;
-        if (D >= 64 || dim < D) part_acc[pi * D + dim] = num[dd];
+#ifndef ATTN_ABLATE_PARTIAL_STORES
+        if (D >= 64 || dim < D) st_agent(&part_acc[pi * D + dim], num[dd]);
+#endif
       }
       if (lane == 0) {
-        part_ml[pi * 2] = mx;
-        part_ml[pi * 2 + 1] = den;
+        st_agent(&part_ml[pi * 2], mx);
+        st_agent(&part_ml[pi * 2 + 1], den);
       }
     }
   }
-}
-
-// Merge the chunk-group partials of one (row, query head): out = sum_c 2^(m_c - m*) acc_c / sum_c 2^(m_c - m*) l_c.
-template <int D>
-__global__ void k_attn_merge(const int* __restrict__ row_pos, const int* __restrict__ row_wstart, int Hq,
-                             const float* __restrict__ part_acc, const float* __restrict__ part_ml,
-                             void* __restrict__ out, int out_fp32, int chunk_tokens) {
-  const int row = blockIdx.x, head = blockIdx.y, dim = threadIdx.x;
-  const int ctx = row_pos[row] + 1;
-  const int n = ((ctx + chunk_tokens - 1) / chunk_tokens + ATTN_GROUP - 1) / ATTN_GROUP;
-  if (n == 1) return;
-  const int ws = row_wstart[row];
-  float mx = NEG_BIG;
-  for (int c = 0; c < n; ++c) mx = fmaxf(mx, part_ml[((size_t)(ws + c) * Hq + head) * 2]);
-  float num = 0.f, den = 0.f;
-  int c = 0;
-  for (; c + 4 <= n; c += 4) {                 // four independent partials in flight
-    float a[4], mm[4], ll[4];
+  if (ngroups == 1) return;                       // uniform over the workgroup
+  // ---- a row of several groups: the group that arrives last merges them all (log-sum-exp merge in group order, so the
+  // result does not depend on which one that is).  Every thread waits until its own partial stores have completed
+  // (they are write-through, see st_agent), the barrier collects the workgroup, then one thread counts the arrival;
+  // the last group reads the others' partials with agent-scope loads.  The counter returns to zero for the next launch.
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (threadIdx.x == 0) last_s = atomicAdd(&row_cnt[row * Hkv + kvh], 1) == ngroups - 1;
+  __syncthreads();
+  if (!last_s) return;
+  // work item of group c: the row's full groups are consecutive from ws.x, a last shorter group sits at ws.y
+  const int2 ws = row_wstart[row];
+  const int nfull = ctx / (ATTN_GROUP * chunk_tokens);
+  for (int h = w; h < G; h += ATTN_GROUP) {
+    const int head = kvh * G + h;
+    float mx = NEG_BIG;
+    for (int c = 0; c < ngroups; ++c)
+      mx = fmaxf(mx, ld_agent(&part_ml[((size_t)(c < nfull ? ws.x + c : ws.y) * Hq + head) * 2]));
+    float den = 0.f, num[DPL];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const size_t pi = (size_t)(ws + c + u) * Hq + head;
-      mm[u] = part_ml[pi * 2];
-      ll[u] = part_ml[pi * 2 + 1];
-      a[u] = part_acc[pi * D + dim];
+    for (int dd = 0; dd < DPL; ++dd) num[dd] = 0.f;
+    for (int c = 0; c < ngroups; ++c) {           // fixed order: group 0, 1, ..
+      const size_t pi = (size_t)(c < nfull ? ws.x + c : ws.y) * Hq + head;
+      const float wgt = __builtin_amdgcn_exp2f(ld_agent(&part_ml[pi * 2]) - mx);
+      den += wgt * ld_agent(&part_ml[pi * 2 + 1]);
+#pragma unroll
+      for (int dd = 0; dd < DPL; ++dd) {
+        const int dim = lane + dd * 64;
+        if (D >= 64 || dim < D) num[dd] += wgt * ld_agent(&part_acc[pi * D + dim]);
+      }
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {              // fixed order: the result does not depend on scheduling
-      const float wgt = __builtin_amdgcn_exp2f(mm[u] - mx);
-      den += wgt * ll[u];
-      num += wgt * a[u];
+    for (int dd = 0; dd < DPL; ++dd) {
+      const int dim = lane + dd * 64;
+      if (D >= 64 || dim < D) {
+        const size_t o = ((size_t)row * Hq + head) * D + dim;
+        if (out_fp32) ((float*)out)[o] = num[dd] / den;
+        else ((uint16_t*)out)[o] = f2bf(num[dd] / den);
+      }
     }
   }
-  for (; c < n; ++c) {
-    const size_t pi = (size_t)(ws + c) * Hq + head;
-    const float wgt = __builtin_amdgcn_exp2f(part_ml[pi * 2] - mx);
-    den += wgt * part_ml[pi * 2 + 1];
-    num += wgt * part_acc[pi * D + dim];
-  }
-  const size_t o = ((size_t)row * Hq + head) * D + dim;
-  if (out_fp32) ((float*)out)[o] = num / den;
-  else ((uint16_t*)out)[o] = f2bf(num / den);
+  if (threadIdx.x == 0) row_cnt[row * Hkv + kvh] = 0;
 }
 
 template <int D>
@@ -274,18 +300,19 @@ int attn_supported(int head_dim, int group) {
 template <int D, int G>
 static void launch_attn_t(const AttnArgs& a, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   const float scale = 1.4426950408889634f / sqrtf((float)D);
+#if ATTN_KVH_FASTEST
+  dim3 grid(a.Hkv, a.n_work);
+#else
   dim3 grid(a.n_work, a.Hkv);
+#endif
   if (ev0) (void)hipEventRecord(ev0, st);
-  hipLaunchKernelGGL((k_decode_attn<D, G>), grid, dim3(256), 0, st, (const uint8_t*)a.pool, (const uint16_t*)a.q,
-                     a.page_table, a.max_pages, a.work, a.Hkv, a.part_acc, a.part_ml, a.out,
+  hipLaunchKernelGGL((k_decode_attn<D, G>), grid, dim3(64 * ATTN_GROUP), 0, st, (const uint8_t*)a.pool, (const uint16_t*)a.q,
+                     a.page_table, a.max_pages, a.work, a.row_wstart, a.Hkv, a.part_acc, a.part_ml, a.row_cnt, a.out,
                      a.out_fp32, scale, a.chunk_tokens);
   if (ev1) (void)hipEventRecord(ev1, st);
-  if (a.need_merge)
-    hipLaunchKernelGGL((k_attn_merge<D>), dim3(a.n_rows, a.Hkv * G), dim3(D), 0, st, a.row_pos, a.row_wstart,
-                       a.Hkv * G, a.part_acc, a.part_ml, a.out, a.out_fp32, a.chunk_tokens);
 }
 
-// ev0 / ev1 (nullable) bracket the main kernel only, not the merge.
+// ev0 / ev1 (nullable) bracket the kernel.
 void launch_decode_attn(const AttnArgs& a, int head_dim, int group, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   if (a.n_work <= 0) return;
   if (head_dim == 128 && group == 4) launch_attn_t<128, 4>(a, st, ev0, ev1);

@@ -11,10 +11,14 @@
 // at five to eight; with little context in flight the floor of 128 tokens beats 256 by 5 % and 64 loses again):
 // fine enough that the end of the launch stays busy, and small in the tail drain so that a few long rollouts still
 // spread over the chip.
+#ifndef ATTN_GROUP_CHUNKS
 #define ATTN_GROUP_CHUNKS 4
+#endif
 #define ATTN_CHUNK_MIN 128
 #define ATTN_CHUNK_MAX 1024         // 64 pages: their ids fit one register across a wavefront
-#define ATTN_TARGET_ITEMS 16384     // 256 CUs x 4 SIMDs x 3 resident waves x 5.3 rounds
+#ifndef ATTN_TARGET_ITEMS
+#define ATTN_TARGET_ITEMS 12288     // 256 CUs x 4 SIMDs x 3 resident waves x 4 rounds
+#endif
 __host__ __device__ __forceinline__ int attn_pick_chunk(unsigned long long total_ctx, int n_kv_heads) {
   unsigned long long c = (total_ctx * (unsigned long long)n_kv_heads + ATTN_TARGET_ITEMS - 1) / ATTN_TARGET_ITEMS;
   c = (c + 63) / 64 * 64;
@@ -64,3 +68,29 @@ __device__ __forceinline__ uint4 ld_stream16(const void* p) {
 
 // bytes of one (page, kv head) block: K then V, bf16
 __host__ __device__ __forceinline__ size_t kv_block_bytes(int head_dim) { return (size_t)2 * PAGE_TOKENS * head_dim * 2; }
+
+// Philox4x32-10 (Salmon et al., SC'11): first output word for counter (c0, c1, c2, c3) under key (k0, k1).
+__device__ __forceinline__ uint32_t philox4x32_10_word0(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                                       uint32_t k1) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    c0 = hi1 ^ c1 ^ k0;
+    c1 = lo1;
+    c2 = hi0 ^ c3 ^ k1;
+    c3 = lo0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  return c0;
+}
+
+// The uniform behind the Gumbel-max draw of vocabulary column `col` for token `tok_index` of sequence `seq_id`:
+// (top 24 bits of the first Philox word + 1/2) * 2^-24, strictly inside (0, 1).
+__device__ __forceinline__ float gumbel_uniform(uint32_t col, uint32_t tok_index, unsigned long long seq_id,
+                                                unsigned long long seed) {
+  const uint32_t w = philox4x32_10_word0(col, tok_index, (uint32_t)seq_id, (uint32_t)(seq_id >> 32), (uint32_t)seed,
+                                         (uint32_t)(seed >> 32));
+  return ((float)(w >> 8) + 0.5f) * 5.9604644775390625e-8f;
+}

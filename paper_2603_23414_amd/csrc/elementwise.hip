@@ -155,29 +155,13 @@ __global__ __launch_bounds__(1024) void k_rope_kvwrite(const float* __restrict__
   }
 }
 
-// Philox4x32-10 (Salmon et al., SC'11): first output word for counter (c0, c1, c2, c3) under key (k0, k1).
-__device__ __forceinline__ uint32_t philox4x32_10_word0(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
-                                                       uint32_t k1) {
-#pragma unroll
-  for (int r = 0; r < 10; ++r) {
-    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
-    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
-    c0 = hi1 ^ c1 ^ k0;
-    c1 = lo1;
-    c2 = hi0 ^ c3 ^ k1;
-    c3 = lo0;
-    k0 += 0x9E3779B9u;
-    k1 += 0xBB67AE85u;
-  }
-  return c0;
-}
-
 // Per row of fp32 logits: the emitted-token candidate and a log-sum-exp.
 //   greedy (inv_temp == 0): arg-max with the lowest index on ties, lse of the logits;
 //   sampling: Gumbel-max draw from softmax(logits * inv_temp) -- argmax_j logits_j * inv_temp - log(-log u_j), with
 //   u_j from Philox4x32-10 at counter (j, token index, seq_id) under the sample seed -- and the lse of the scaled logits.
 __global__ __launch_bounds__(1024) void k_argmax_lse(const float* __restrict__ logits, int V, int* __restrict__ row_argmax,
-                                                     float* __restrict__ row_lse, float inv_temp,
+                                                     float* __restrict__ row_lse, float* __restrict__ row_ztok,
+                                                     float* __restrict__ row_zeos, int eos_id, float inv_temp,
                                                      unsigned long long seed, const int* __restrict__ row_slot,
                                                      const int* __restrict__ slot_seq,
                                                      const unsigned long long* __restrict__ seq_id,
@@ -189,15 +173,13 @@ __global__ __launch_bounds__(1024) void k_argmax_lse(const float* __restrict__ l
   const float* x = logits + (size_t)blockIdx.x * V;
   const bool sampling = inv_temp > 0.f;
   const float scale = sampling ? inv_temp : 1.f;
-  uint32_t c1 = 0, c2 = 0, c3 = 0;
+  uint32_t tok_index = 0;
+  unsigned long long id = 0;
   if (sampling) {
     const int sidx = slot_seq[row_slot[blockIdx.x]];
-    const unsigned long long id = seq_id[sidx];
-    c1 = (uint32_t)seq_gen_len[sidx];
-    c2 = (uint32_t)id;
-    c3 = (uint32_t)(id >> 32);
+    id = seq_id[sidx];
+    tok_index = (uint32_t)seq_gen_len[sidx];
   }
-  const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
   float best = -INFINITY, mx = -INFINITY;
   int bi = 0x7fffffff;
   // every thread walks its elements in ascending index order, so its first hit is its lowest index
@@ -205,10 +187,7 @@ __global__ __launch_bounds__(1024) void k_argmax_lse(const float* __restrict__ l
     const float z = xi * scale;
     mx = fmaxf(mx, z);
     float v = z;
-    if (sampling) {
-      const float u = ((float)(philox4x32_10_word0((uint32_t)i, c1, c2, c3, k0, k1) >> 8) + 0.5f) * 5.9604644775390625e-8f;
-      v = z - __logf(-__logf(u));
-    }
+    if (sampling) v = z - __logf(-__logf(gumbel_uniform((uint32_t)i, tok_index, id, seed)));
     if (v > best) { best = v; bi = i; }
   };
   const bool vec = (V & 3) == 0;     // rows are 16-byte aligned: four vectors of four logits in flight per thread
@@ -273,6 +252,8 @@ __global__ __launch_bounds__(1024) void k_argmax_lse(const float* __restrict__ l
     for (int k = 0; k < 16; ++k) t += s_sum[k];
     row_argmax[blockIdx.x] = bi;
     row_lse[blockIdx.x] = mx + __logf(t);
+    row_ztok[blockIdx.x] = x[bi] * scale;
+    row_zeos[blockIdx.x] = x[eos_id] * scale;
   }
 }
 
@@ -354,11 +335,56 @@ void launch_rope_kvwrite(const float* part, int S, size_t part_stride, const flo
     hipLaunchKernelGGL(k_rope_kvwrite, dim3(R), dim3(1024), 0, st, part, S, part_stride, bias, row_slot, row_pos,
                        (const float2*)cs_table, (uint16_t*)q_out, (uint8_t*)pool, page_table, max_pages, Hq, Hkv, d);
 }
-void launch_argmax_lse(const float* logits, int V, int* row_argmax, float* row_lse, int R, const SchedDev* sched,
-                       hipStream_t st) {
+void launch_argmax_lse(const float* logits, int V, int* row_argmax, float* row_lse, float* row_ztok, float* row_zeos, int R,
+                       const SchedDev* sched, hipStream_t st) {
   if (R > 0)
-    hipLaunchKernelGGL(k_argmax_lse, dim3(R), dim3(1024), 0, st, logits, V, row_argmax, row_lse, sched->inv_temp,
-                       sched->sample_seed, sched->row_slot, sched->slot_seq, sched->seq_id, sched->seq_gen_len);
+    hipLaunchKernelGGL(k_argmax_lse, dim3(R), dim3(1024), 0, st, logits, V, row_argmax, row_lse, row_ztok, row_zeos,
+                       sched->eos_id, sched->inv_temp, sched->sample_seed, sched->row_slot, sched->slot_seq, sched->seq_id,
+                       sched->seq_gen_len);
+}
+
+// Combine the per-tile records the fused LM head left for each row (ascending column order: the first maximum a thread
+// meets is its lowest index, and equal scores across threads go to the lower index).
+__global__ __launch_bounds__(256) void k_lm_reduce(const float4* __restrict__ part_f, const int* __restrict__ part_i,
+                                                   int n_tiles, int* __restrict__ row_argmax,
+                                                   float* __restrict__ row_ztok, float* __restrict__ row_lse) {
+  __shared__ float s_v[4], s_z[4], s_m[4], s_s[4];
+  __shared__ int s_i[4];
+  const int r = blockIdx.x;
+  float bv = -INFINITY, bz = 0.f, mx = -INFINITY, sum = 0.f;
+  int bi = 0x7fffffff;
+  for (int t = threadIdx.x; t < n_tiles; t += 256) {
+    const float4 f = part_f[(size_t)r * n_tiles + t];
+    const int i = part_i[(size_t)r * n_tiles + t];
+    if (f.x > bv || (f.x == bv && i < bi)) { bv = f.x; bi = i; bz = f.y; }
+    const float m2 = fmaxf(mx, f.z);
+    if (m2 > -INFINITY) sum = sum * __expf(mx - m2) + f.w * __expf(f.z - m2);
+    mx = m2;
+  }
+  auto merge = [&](float ov, int oi, float oz, float om, float os) {
+    if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; bz = oz; }
+    const float m2 = fmaxf(mx, om);
+    if (m2 > -INFINITY) sum = sum * __expf(mx - m2) + os * __expf(om - m2);
+    mx = m2;
+  };
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1)
+    merge(__shfl_xor(bv, o, 64), __shfl_xor(bi, o, 64), __shfl_xor(bz, o, 64), __shfl_xor(mx, o, 64), __shfl_xor(sum, o, 64));
+  const int w = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) { s_v[w] = bv; s_i[w] = bi; s_z[w] = bz; s_m[w] = mx; s_s[w] = sum; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    bv = s_v[0]; bi = s_i[0]; bz = s_z[0]; mx = s_m[0]; sum = s_s[0];
+    for (int k = 1; k < 4; ++k) merge(s_v[k], s_i[k], s_z[k], s_m[k], s_s[k]);
+    row_argmax[r] = bi;
+    row_ztok[r] = bz;
+    row_lse[r] = mx + __logf(sum);
+  }
+}
+void launch_lm_reduce(const LmEpi& epi, int M, int* row_argmax, float* row_ztok, float* row_lse, hipStream_t st) {
+  if (M > 0)
+    hipLaunchKernelGGL(k_lm_reduce, dim3(M), dim3(256), 0, st, (const float4*)epi.part_f, (const int*)epi.part_i, epi.n_tiles,
+                       row_argmax, row_ztok, row_lse);
 }
 void launch_gather_rows(const float* src, const int* src_row, float* dst, int dst_row0, int n, int D, hipStream_t st) {
   if (n > 0) hipLaunchKernelGGL(k_gather_rows, dim3(n), dim3(256), 0, st, src, src_row, dst, dst_row0, D);

@@ -79,6 +79,11 @@ struct rollout_ctx {
   float* logits = nullptr;
   int* row_argmax = nullptr;
   float* row_lse = nullptr;
+  float* row_ztok = nullptr;
+  float* row_zeos = nullptr;
+  float4* lm_part_f = nullptr;   // per-(row, column tile) records of the fused LM head
+  int* lm_part_i = nullptr;
+  int lm_tiles = 0;
   int* iota = nullptr;
   // prefill rows + attention workspace
   int *pf_row_slot = nullptr, *pf_row_pos = nullptr, *pf_row_tok = nullptr;
@@ -89,6 +94,7 @@ struct rollout_ctx {
   int* pf_last_host = nullptr;          // pinned
   float* part_acc = nullptr;
   float* part_ml = nullptr;
+  int* attn_row_cnt = nullptr;
   size_t max_work = 0;
   // submit staging (pinned + device)
   SubmitRec* sub_host = nullptr;
@@ -284,7 +290,7 @@ int fill_weights(rollout_ctx* c, const void* weights, size_t weights_bytes) {
 
 // ---- the per-step kernel chain over a set of rows (decode rows or one prefill pass) ---------------------
 void run_layers(rollout_ctx* c, int R, const int* row_slot, const int* row_pos, const int* row_tok, const int4* work,
-                const int* row_wstart, int n_work, int chunk_tokens, bool time_attn, const PfTileHost* pf_tiles = nullptr,
+                const int2* row_wstart, int n_work, int chunk_tokens, bool time_attn, const PfTileHost* pf_tiles = nullptr,
                 int n_tiles = 0) {
   hipStream_t st = c->stream;
   const int D = c->D, F = c->F, Hq = c->Hq, Hkv = c->Hkv, d = c->d, Nqkv = c->Nqkv;
@@ -312,9 +318,9 @@ void run_layers(rollout_ctx* c, int R, const int* row_slot, const int* row_pos, 
     a.Hkv = Hkv;
     a.part_acc = c->part_acc;
     a.part_ml = c->part_ml;
+    a.row_cnt = c->attn_row_cnt;
     a.out = c->attn_out;
     a.out_fp32 = 0;
-    a.need_merge = n_work > R;
     a.chunk_tokens = chunk_tokens;
     if (n_tiles > 0) {
       launch_prefill_attn(pool_l, c->qbuf, pf_tiles, n_tiles, c->sd.page_table, c->max_pages, Hq, Hkv, d, c->attn_out, st);
@@ -412,8 +418,28 @@ int step_impl(rollout_ctx* c, const int32_t* forced_tok, rollout_step_info* info
     }
     if (n_adm > 0) TRY(run_prefill(c, n_dec, n_adm));
     launch_add_rmsnorm(c->h_final, nullptr, 0, 0, c->final_norm, c->cfg.rms_eps, c->x_final, n_rows, c->D, st);
-    launch_gemm(c->x_final, c->lm_head, c->logits, n_rows, c->V, c->D, 1, st);
-    launch_argmax_lse(c->logits, c->V, c->row_argmax, c->row_lse, n_rows, &c->sd, st);
+    if (forced_tok) {
+      // teacher forcing reads arbitrary logits: keep the fp32 rows and take the statistics from them
+      launch_gemm(c->x_final, c->lm_head, c->logits, n_rows, c->V, c->D, 1, st);
+      launch_argmax_lse(c->logits, c->V, c->row_argmax, c->row_lse, c->row_ztok, c->row_zeos, n_rows, &c->sd, st);
+    } else {
+      // the rollout step proper: arg-max / Gumbel-max draw, EOS logit and log-sum-exp in the LM head's epilogue
+      LmEpi e;
+      e.scale = c->sd.inv_temp > 0.f ? c->sd.inv_temp : 1.f;
+      e.sampling = c->sd.inv_temp > 0.f ? 1 : 0;
+      e.seed = c->sd.sample_seed;
+      e.eos_id = c->sd.eos_id;
+      e.n_tiles = c->lm_tiles;
+      e.row_slot = c->sd.row_slot;
+      e.slot_seq = c->sd.slot_seq;
+      e.seq_id = c->sd.seq_id;
+      e.seq_gen_len = c->sd.seq_gen_len;
+      e.part_f = c->lm_part_f;
+      e.part_i = c->lm_part_i;
+      e.row_zeos = c->row_zeos;
+      launch_gemm_lm_fused(c->x_final, c->lm_head, n_rows, c->V, c->D, e, st);
+      launch_lm_reduce(e, n_rows, c->row_argmax, c->row_ztok, c->row_lse, st);
+    }
   }
   launch_sched_emit(c->sd, st);
   TRY(sync_status(c));
@@ -660,6 +686,11 @@ int rollout_init(rollout_ctx** out, const void* weights, size_t weights_bytes, c
     INIT_TRY(dev_alloc(c, &c->logits, Q * V));
     INIT_TRY(dev_alloc(c, &c->row_argmax, Q));
     INIT_TRY(dev_alloc(c, &c->row_lse, Q));
+    INIT_TRY(dev_alloc(c, &c->row_ztok, Q));
+    INIT_TRY(dev_alloc(c, &c->row_zeos, Q));
+    c->lm_tiles = (c->V + 127) / 128;
+    INIT_TRY(dev_alloc(c, &c->lm_part_f, Q * (size_t)c->lm_tiles));
+    INIT_TRY(dev_alloc(c, &c->lm_part_i, Q * (size_t)c->lm_tiles));
     INIT_TRY(dev_alloc(c, &c->iota, R));
     {
       std::vector<int> io(R);
@@ -677,8 +708,12 @@ int rollout_init(rollout_ctx** out, const void* weights, size_t weights_bytes, c
     INIT_TRY(host_alloc(c, &c->pf_last_host, (size_t)2 * PF_ROWS));
     INIT_TRY(dev_alloc(c, &c->part_acc, c->max_work * c->Hq * c->d));
     INIT_TRY(dev_alloc(c, &c->part_ml, c->max_work * c->Hq * 2));
+    INIT_TRY(dev_alloc(c, &c->attn_row_cnt, Q * (size_t)c->Hkv));   // zero now; every attention launch leaves it at zero
+    INIT_HIP(hipMemsetAsync(c->attn_row_cnt, 0, Q * (size_t)c->Hkv * sizeof(int), c->stream));
     s.row_argmax = c->row_argmax;
     s.row_lse = c->row_lse;
+    s.row_ztok = c->row_ztok;
+    s.row_zeos = c->row_zeos;
     s.logits = c->logits;
     INIT_TRY(alloc_weights(c));
     INIT_TRY(fill_weights(c, weights, weights_bytes));
@@ -981,13 +1016,14 @@ int rollout_attn_write_kv(void* pool_dev, uint32_t n_kv_heads, uint32_t head_dim
 }
 
 static inline uint64_t align256(uint64_t x) { return (x + 255) & ~(uint64_t)255; }
-struct AttnWs { uint64_t row_slot, row_pos, row_wstart, work, part_ml, part_acc, total; };
+struct AttnWs { uint64_t row_slot, row_pos, row_wstart, row_cnt, work, part_ml, part_acc, total; };
 static AttnWs attn_ws_layout(uint32_t n, uint64_t max_work, uint32_t Hq, uint32_t d) {
   AttnWs w;
   uint64_t o = 0;
   w.row_slot = o; o = align256(o + 4ull * n);
   w.row_pos = o; o = align256(o + 4ull * n);
-  w.row_wstart = o; o = align256(o + 4ull * n);
+  w.row_wstart = o; o = align256(o + 8ull * n);
+  w.row_cnt = o; o = align256(o + 4ull * n * Hq);     // n * n_kv_heads counters (n_kv_heads <= n_q_heads)
   w.work = o; o = align256(o + 16ull * max_work);
   w.part_ml = o; o = align256(o + 8ull * max_work * Hq);
   w.part_acc = o; o = align256(o + 4ull * max_work * Hq * d);
@@ -1012,20 +1048,35 @@ int rollout_attn_plan(const int32_t* ctx_len, uint32_t n, uint32_t n_q_heads, ui
   const int chunk = attn_pick_chunk(total, (int)n_kv_heads);
   const AttnWs w = attn_ws_layout(n, max_work, n_q_heads, head_dim);
   if (w.total > workspace_bytes) return fail(nullptr, ROLLOUT_EINVAL, "workspace too small");
-  std::vector<int> rs(n), rp(n), ws(n);
-  std::vector<int4> work;
-  work.reserve(max_work);
+  std::vector<int> rs(n), rp(n);
+  std::vector<int2> ws(n);
+  // full groups first (consecutive per sequence), then the shorter last groups in descending length (ties: ascending
+  // sequence), so that the launch ends on its smallest items
+  const int gt = ATTN_GROUP_CHUNKS * chunk;
+  std::vector<int> rem_order;
+  int n_full = 0;
   for (uint32_t i = 0; i < n; ++i) {
     rs[i] = (int)i;
     rp[i] = ctx_len[i] - 1;
-    ws[i] = (int)work.size();
-    const int nch = attn_row_items(ctx_len[i], chunk);
-    for (int ch = 0; ch < nch; ++ch) work.push_back(make_int4((int)i, ch, (int)i, ctx_len[i]));
+    ws[i].x = n_full;
+    n_full += ctx_len[i] / gt;
+    if (ctx_len[i] % gt) rem_order.push_back((int)i);
   }
+  std::stable_sort(rem_order.begin(), rem_order.end(), [&](int a, int b) { return ctx_len[a] % gt > ctx_len[b] % gt; });
+  std::vector<int4> work((size_t)n_full + rem_order.size());
+  for (uint32_t i = 0; i < n; ++i)
+    for (int c = 0; c < ctx_len[i] / gt; ++c) work[ws[i].x + c] = make_int4((int)i, c, (int)i, ctx_len[i]);
+  for (size_t k = 0; k < rem_order.size(); ++k) {
+    const int i = rem_order[k];
+    ws[i].y = n_full + (int)k;
+    work[ws[i].y] = make_int4(i, ctx_len[i] / gt, i, ctx_len[i]);
+  }
+  if (work.size() > max_work) return fail(nullptr, ROLLOUT_EINVAL, "work list larger than planned");
   uint8_t* base = (uint8_t*)workspace_dev;
   if (hipMemcpy(base + w.row_slot, rs.data(), 4ull * n, hipMemcpyHostToDevice) != hipSuccess ||
       hipMemcpy(base + w.row_pos, rp.data(), 4ull * n, hipMemcpyHostToDevice) != hipSuccess ||
-      hipMemcpy(base + w.row_wstart, ws.data(), 4ull * n, hipMemcpyHostToDevice) != hipSuccess ||
+      hipMemcpy(base + w.row_wstart, ws.data(), 8ull * n, hipMemcpyHostToDevice) != hipSuccess ||
+      hipMemset(base + w.row_cnt, 0, 4ull * n * n_q_heads) != hipSuccess ||
       hipMemcpy(base + w.work, work.data(), 16ull * work.size(), hipMemcpyHostToDevice) != hipSuccess)
     return fail(nullptr, ROLLOUT_EDEVICE, "hipMemcpy failed");
   *n_work = (uint32_t)work.size();
@@ -1054,15 +1105,15 @@ int rollout_attn_decode(const void* pool_dev, uint32_t n_q_heads, uint32_t n_kv_
   a.page_table = page_table_dev;
   a.max_pages = (int)max_pages;
   a.work = (const int4*)(base + w.work);
-  a.row_wstart = (const int*)(base + w.row_wstart);
+  a.row_wstart = (const int2*)(base + w.row_wstart);
   a.n_work = (int)n_work;
   a.n_rows = (int)n;
   a.Hkv = (int)n_kv_heads;
   a.part_ml = (float*)(base + w.part_ml);
+  a.row_cnt = (int*)(base + w.row_cnt);
   a.part_acc = (float*)(base + w.part_acc);
   a.out = out_dev;
   a.out_fp32 = out_fp32;
-  a.need_merge = n_work > n;
   a.chunk_tokens = (int)chunk_tokens;
   launch_decode_attn(a, (int)head_dim, (int)(n_q_heads / n_kv_heads), (hipStream_t)stream);
   return hipGetLastError() == hipSuccess ? ROLLOUT_OK : fail(nullptr, ROLLOUT_EDEVICE, "kernel launch failed");

@@ -39,9 +39,15 @@ __device__ __forceinline__ u32x4 ldw(const uint16_t* p) {
 // act[M, N/2].  No split-K in that mode.
 // STREAM = true reads W with streaming (non-temporal) loads: right when every weight byte is used once per launch
 // (M <= 256), wrong when several row blocks re-read the same W slab from L2 (prefill).
+// EPI = 2 (greedy) / 3 (sampling): the LM head with the emit statistics in its epilogue (no logits are stored).  The two MFMA operands are
+// swapped, which transposes the accumulator tile at no cost (both fragments have the same register layout): a lane
+// then owns ONE row (lane % 32) and 16 of the wave's 32 columns, so the per-row arg-max / Gumbel-max draw, the
+// maximum and the sum of exponentials are plain per-lane loops over registers; the two half-waves, then the four
+// wavefronts, are merged in ascending column order, and the workgroup leaves one record per row.
 template <int MI, int EPI, bool STREAM>
 __global__ __launch_bounds__(256, 2) void k_gemm_bf16(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
-                                                      float* __restrict__ C, int M, int N, int K, int kb_per_split) {
+                                                      float* __restrict__ C, int M, int N, int K, int kb_per_split,
+                                                      LmEpi lm) {
   constexpr int BM = 32 * MI;
   __shared__ __align__(16) uint16_t a_lds[2][BM * LDS_ROW];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -109,7 +115,8 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16(const uint16_t* __restrict
 #pragma unroll
           for (int i = 0; i < MI; ++i) {
             const u32x4 av = *(const u32x4*)(al + i * 32 * LDS_ROW + j * 8);
-            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av), bf, acc[i], 0, 0, 0);
+            if (EPI >= 2) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf, __builtin_bit_cast(bf16x8_t, av), acc[i], 0, 0, 0);
+            else acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av), bf, acc[i], 0, 0, 0);
           }
         }
 #pragma unroll
@@ -119,6 +126,76 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16(const uint16_t* __restrict
     }
   }
 
+  if (EPI >= 2) {
+    constexpr bool SAMPLING = EPI == 3;                   // a separate instantiation: the generator is 128 x inlined
+    // transposed tile: element j of lane -> column n_base + (j/4)*8 + (lane/32)*4 + j%4 (ascending in j), row lane%32
+    float* rec_f = (float*)&a_lds[0][0];                  // [4 waves][BM rows][4]; the A tiles are dead (last barrier passed)
+    int* rec_i = (int*)(rec_f + 4 * BM * 4);              // [4 waves][BM rows]
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+      const int m = m_base + i * 32 + (lane & 31);
+      uint32_t tok_index = 0;
+      unsigned long long sid = 0;
+      if (SAMPLING && m < M) {
+        const int sidx = lm.slot_seq[lm.row_slot[m]];
+        sid = lm.seq_id[sidx];
+        tok_index = (uint32_t)lm.seq_gen_len[sidx];
+      }
+      float bv = -INFINITY, bz = 0.f, mx = -INFINITY;
+      int bi = 0x7fffffff;
+      float z[16];
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int n = n_base + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
+        const bool valid = n < N;
+        const float zz = valid ? acc[i][j] * lm.scale : -INFINITY;
+        float v = zz;
+        if (SAMPLING && valid) v = zz - __logf(-__logf(gumbel_uniform((uint32_t)n, tok_index, sid, lm.seed)));
+        if (v > bv) { bv = v; bi = n; bz = zz; }          // ascending columns: the first maximum is the lowest index
+        mx = fmaxf(mx, zz);
+        z[j] = zz;
+        if (n == lm.eos_id && m < M) lm.row_zeos[m] = zz;
+      }
+      float sum = 0.f;
+      if (mx > -INFINITY) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) sum += __expf(z[j] - mx);   // exp(-inf) = 0 for columns past the vocabulary
+      }
+      // the other half-wave holds the interleaved other 16 columns of the same row
+      {
+        const float ov = __shfl_xor(bv, 32, 64), oz = __shfl_xor(bz, 32, 64), om = __shfl_xor(mx, 32, 64),
+                    os = __shfl_xor(sum, 32, 64);
+        const int oi = __shfl_xor(bi, 32, 64);
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; bz = oz; }
+        const float m2 = fmaxf(mx, om);
+        if (m2 > -INFINITY) sum = sum * __expf(mx - m2) + os * __expf(om - m2);
+        mx = m2;
+      }
+      if (lane < 32) {
+        const int row = i * 32 + lane;
+        *(float4*)(rec_f + ((size_t)w * BM + row) * 4) = make_float4(bv, bz, mx, sum);
+        rec_i[w * BM + row] = bi;
+      }
+    }
+    __syncthreads();
+    if (tid < BM && m_base + tid < M) {                    // one thread per row: the four wavefronts in column order
+      float4 f = *(const float4*)(rec_f + (size_t)tid * 4);
+      int bi = rec_i[tid];
+#pragma unroll
+      for (int u = 1; u < 4; ++u) {
+        const float4 o = *(const float4*)(rec_f + ((size_t)u * BM + tid) * 4);
+        const int oi = rec_i[u * BM + tid];
+        if (o.x > f.x || (o.x == f.x && oi < bi)) { f.x = o.x; f.y = o.y; bi = oi; }
+        const float m2 = fmaxf(f.z, o.z);
+        if (m2 > -INFINITY) f.w = f.w * __expf(f.z - m2) + o.w * __expf(o.z - m2);
+        f.z = m2;
+      }
+      const size_t o = (size_t)(m_base + tid) * lm.n_tiles + blockIdx.x;
+      lm.part_f[o] = f;
+      lm.part_i[o] = bi;
+    }
+    return;
+  }
   // C fragment: element j of lane -> row (j/4)*8 + (lane/32)*4 + j%4, col lane%32
   const int n_out = n_base + (lane & 31);
   if (EPI == 1) {
@@ -589,11 +666,32 @@ static void launch_gemm_t(const uint16_t* a, const uint16_t* w, float* C, int M,
     return;
   }
   switch (p.mi) {   // a single row block (every decode launch) streams W
-    case 1: hipLaunchKernelGGL((k_gemm_bf16<1, EPI, true>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
-    case 2: hipLaunchKernelGGL((k_gemm_bf16<2, EPI, true>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
-    case 4: hipLaunchKernelGGL((k_gemm_bf16<4, EPI, true>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
-    default: hipLaunchKernelGGL((k_gemm_bf16<8, EPI, true>), grid, dim3(256), 0, st, a, w, C, M, N, K, per); break;
+    case 1: hipLaunchKernelGGL((k_gemm_bf16<1, EPI, true>), grid, dim3(256), 0, st, a, w, C, M, N, K, per, LmEpi{}); break;
+    case 2: hipLaunchKernelGGL((k_gemm_bf16<2, EPI, true>), grid, dim3(256), 0, st, a, w, C, M, N, K, per, LmEpi{}); break;
+    case 4: hipLaunchKernelGGL((k_gemm_bf16<4, EPI, true>), grid, dim3(256), 0, st, a, w, C, M, N, K, per, LmEpi{}); break;
+    default: hipLaunchKernelGGL((k_gemm_bf16<8, EPI, true>), grid, dim3(256), 0, st, a, w, C, M, N, K, per, LmEpi{}); break;
   }
+}
+
+// The LM head with fused emit statistics: always the base kernel (a single K split), one row block of up to 256 rows
+// per blockIdx.y.  epi.n_tiles must equal ceil(N / 128); part_f / part_i hold M * n_tiles records.
+void launch_gemm_lm_fused(const void* A, const void* W, int M, int N, int K, const LmEpi& epi, hipStream_t st) {
+  if (M <= 0) return;
+  const uint16_t* a = (const uint16_t*)A;
+  const uint16_t* w = (const uint16_t*)W;
+  const int mi = M <= 32 ? 1 : M <= 64 ? 2 : M <= 128 ? 4 : 8;
+  const dim3 grid((N + 127) / 128, (M + 32 * mi - 1) / (32 * mi), 1);
+  const int per = K / GEMM_BK;
+#define LM_LAUNCH(MI_)                                                                                                   \
+  if (epi.sampling) hipLaunchKernelGGL((k_gemm_bf16<MI_, 3, true>), grid, dim3(256), 0, st, a, w, nullptr, M, N, K, per, epi); \
+  else hipLaunchKernelGGL((k_gemm_bf16<MI_, 2, true>), grid, dim3(256), 0, st, a, w, nullptr, M, N, K, per, epi)
+  switch (mi) {
+    case 1: LM_LAUNCH(1); break;
+    case 2: LM_LAUNCH(2); break;
+    case 4: LM_LAUNCH(4); break;
+    default: LM_LAUNCH(8); break;
+  }
+#undef LM_LAUNCH
 }
 
 void launch_gemm(const void* A, const void* W, float* C, int M, int N, int K, int S, hipStream_t st) {

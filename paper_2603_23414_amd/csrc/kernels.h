@@ -12,14 +12,17 @@ struct AttnArgs {
   const int* row_pos;      // position of the query token (context = pos + 1)
   const int* page_table;   // int32 [slots][max_pages]
   int max_pages;
-  const int4* work;        // (row, chunk, page-table row, context length) items: all a wavefront needs to start
-  const int* row_wstart;   // first work item of each row
+  const int4* work;        // (row, group, page-table row, context length) items: all a workgroup needs to start; full
+                           // groups first, then the shorter last groups of the rows in descending length, so that the
+                           // launch ends on its smallest items
+  const int2* row_wstart;  // work items of each row: .x = first of its full groups (consecutive), .y = its last, shorter group
   int n_work, n_rows, Hkv;
   float* part_acc;         // [n_work][Hq][d]
   float* part_ml;          // [n_work][Hq][2]
+  int* row_cnt;            // [n_rows][Hkv] arrival counters of rows that span several work items: zero before the
+                           // first launch, left at zero by every launch
   void* out;               // [n_rows][Hq*d], bf16 or fp32
   int out_fp32;
-  int need_merge;          // some row spans more than one chunk
   int chunk_tokens;        // cached tokens per work item (multiple of 64, at most 1024)
 };
 int attn_supported(int head_dim, int group);
@@ -39,6 +42,27 @@ int gemm_pick_splits(int M, int N, int K);
 const char* gemm_kernel_name(int M, int N, int K, int S, int epi);
 void launch_gemm(const void* A, const void* W, float* C, int M, int N, int K, int S, hipStream_t st);
 void launch_gemm_swiglu(const void* A, const void* W, void* act, int M, int N, int K, hipStream_t st);
+// The LM head with the emit statistics taken in its epilogue, so that no logits row is ever written: per row the
+// candidate token (arg-max with the lowest index on ties, or the Gumbel-max draw when sampling), its scaled logit, the
+// scaled logit of the EOS column and the log-sum-exp of the scaled logits.  Each workgroup (128 columns) leaves one
+// partial record per row; lm_reduce combines a row's records in ascending column order (deterministic).
+struct LmEpi {
+  float scale;                       // logits multiplier: 1 / temperature when sampling, else 1
+  int sampling;
+  unsigned long long seed;           // key of the counter-based generator
+  int eos_id;
+  int n_tiles;                       // column tiles = workgroups along the vocabulary
+  const int* row_slot;               // sampling only: row -> slot -> sequence -> (seq_id, tokens generated so far)
+  const int* slot_seq;
+  const unsigned long long* seq_id;
+  const int* seq_gen_len;
+  float4* part_f;                    // [rows][n_tiles]: best perturbed score, its scaled logit, max scaled logit, sum exp
+  int* part_i;                       // [rows][n_tiles]: column of the best score
+  float* row_zeos;                   // [rows]: scaled logit of the EOS column
+};
+void launch_gemm_lm_fused(const void* A, const void* W, int M, int N, int K, const LmEpi& epi, hipStream_t st);
+void launch_lm_reduce(const LmEpi& epi, int M, int* row_argmax, float* row_ztok, float* row_lse, hipStream_t st);
+
 // row-major [N, K] -> the packed fragment layout the GEMM kernels read (N * K elements; N a multiple of 32)
 void launch_pack_weights(const void* src, void* dst, size_t N, size_t K, hipStream_t st);
 void launch_reduce_splits(const float* part, float* c, size_t mn, int S, hipStream_t st);
@@ -52,8 +76,8 @@ void launch_rope_kvwrite(const float* part, int S, size_t part_stride, const flo
                          const int* row_pos, const void* cs_table, void* q_out, void* pool, const int* page_table,
                          int max_pages, int Hq, int Hkv, int d, int R, hipStream_t st);
 // greedy (inv_temp == 0) or Gumbel-max sampling; row_lse is the log-sum-exp of logits * inv_temp (of logits if greedy)
-void launch_argmax_lse(const float* logits, int V, int* row_argmax, float* row_lse, int R, const SchedDev* sched,
-                       hipStream_t st);
+void launch_argmax_lse(const float* logits, int V, int* row_argmax, float* row_lse, float* row_ztok, float* row_zeos, int R,
+                       const SchedDev* sched, hipStream_t st);
 void launch_gather_rows(const float* src, const int* src_row, float* dst, int dst_row0, int n, int D, hipStream_t st);
 
 // ---- scheduler state (device side of the rollout state manager / stateful buffer, Sec. 3.3) ----------
@@ -90,11 +114,14 @@ struct SchedDev {
   int *grp_nshared, *grp_ref, *grp_version, *grp_pages;   // grp_pages: [max_seqs][max_shared]
   int max_shared;
   int *q_ring, *free_stack, *fin_list;
-  int *row_slot, *row_pos, *row_tok, *row_wstart;
+  int *row_slot, *row_pos, *row_tok;
+  int2* row_wstart;
   int4* work;
   const int* row_argmax;
   const float* row_lse;
-  const float* logits;
+  const float* row_ztok;   // scaled logit of the candidate token of each row
+  const float* row_zeos;   // scaled logit of the EOS column of each row
+  const float* logits;     // fp32 logits rows: only the teacher-forced path has them
   const int* forced_tok;   // nullable
   int* status;
 };

@@ -45,8 +45,8 @@ __device__ __forceinline__ void q_push_front(const SchedDev& d, int sidx) {
 
 // Rebuild the decode row list (ascending slot order = order-preserving compaction) and the attention work
 // list for the next step, then publish the status block.  Called by all threads at the end of a kernel.
-__device__ void rebuild_rows_and_status(const SchedDev& d, int* sh, int r_this_step, int n_fin_step, int n_pre_step,
-                                        int n_adm) {
+__device__ void rebuild_rows_and_status(const SchedDev& d, int* sh, int* big /* 1024 ints of LDS */, int r_this_step,
+                                        int n_fin_step, int n_pre_step, int n_adm) {
   const int t = threadIdx.x;
   int sidx = -1, pos = 0;
   if (t < d.Q && (sidx = d.slot_seq[t]) >= 0) pos = d.seq_prompt_len[sidx] + d.seq_gen_len[sidx] - 1;
@@ -56,17 +56,32 @@ __device__ void rebuild_rows_and_status(const SchedDev& d, int* sh, int r_this_s
   block_scan_excl(sidx >= 0 ? ((pos + 1) >> 16) : 0, &hi_tot, sh);
   const unsigned long long ctx_total = (unsigned long long)lo_tot + ((unsigned long long)hi_tot << 16);
   const int chunk = attn_pick_chunk(ctx_total, d.Hkv);
-  const int nch = sidx >= 0 ? attn_row_items(pos + 1, chunk) : 0;
-  int n_active, n_work;
+  // work items: a row's full groups (ATTN_GROUP_CHUNKS chunks each) go to the front of the list, its last, shorter group
+  // to the back part, which is ordered by descending length (ties: ascending slot) -- the dispatcher hands out
+  // workgroups in list order, so the launch ends on its smallest items instead of on whatever the last slots hold
+  const int gt = ATTN_GROUP_CHUNKS * chunk;
+  const int nfull = sidx >= 0 ? (pos + 1) / gt : 0;
+  const int rem = sidx >= 0 ? (pos + 1) % gt : 0;
+  big[t] = rem;
+  int n_active, n_full;
   const int rank = block_scan_excl(sidx >= 0 ? 1 : 0, &n_active, sh);
-  const int wstart = block_scan_excl(nch, &n_work, sh);
+  const int fstart = block_scan_excl(nfull, &n_full, sh);   // (its barriers also publish big[])
+  int n_rem = 0, rrank = 0;
+  for (int j = 0; j < d.Q; ++j) {
+    const int rj = big[j];
+    n_rem += rj > 0;
+    rrank += rj > rem || (rj == rem && rj > 0 && j < t);
+  }
+  const int n_work = n_full + n_rem;
   if (sidx >= 0) {
     d.row_slot[rank] = t;
     d.row_pos[rank] = pos;
     d.row_tok[rank] = d.seq_tokens[(size_t)sidx * d.tok_stride + pos];
-    d.row_wstart[rank] = wstart;
-    for (int c = 0; c < nch; ++c) d.work[wstart + c] = make_int4(rank, c, t, pos + 1);
+    d.row_wstart[rank] = make_int2(fstart, n_full + rrank);
+    for (int c = 0; c < nfull; ++c) d.work[fstart + c] = make_int4(rank, c, t, pos + 1);
+    if (rem > 0) d.work[n_full + rrank] = make_int4(rank, nfull, t, pos + 1);
   }
+  __syncthreads();                                          // big[] is the caller's scratch again
   if (t == 0) {
     d.sc[SC_NDEC] = n_active;
     d.sc[SC_NPRE] = 0;
@@ -249,8 +264,16 @@ __global__ __launch_bounds__(1024) void k_sched_emit(SchedDev d) {
     const bool forced = tgt > 0 && g + 1 == tgt;
     int tok = forced ? d.eos_id : (d.no_model ? 0 : d.row_argmax[r]);
     if (d.forced_tok && d.forced_tok[t] >= 0) tok = d.forced_tok[t];
-    const float lscale = d.inv_temp > 0.f ? d.inv_temp : 1.f;   // log-prob under the distribution that was sampled
-    const float lp = d.no_model ? 0.f : d.logits[(size_t)r * d.V + tok] * lscale - d.row_lse[r];
+    // log-prob under the distribution that was sampled: scaled logit of the emitted token minus the log-sum-exp.  The
+    // candidate's and the EOS column's scaled logits come with the row statistics; only a teacher-forced token needs
+    // the logits row itself (that path keeps it).
+    float lp = 0.f;
+    if (!d.no_model) {
+      const float lscale = d.inv_temp > 0.f ? d.inv_temp : 1.f;
+      const bool taught = d.forced_tok && d.forced_tok[t] >= 0;
+      const float z = taught ? d.logits[(size_t)r * d.V + tok] * lscale : forced ? d.row_zeos[r] : d.row_ztok[r];
+      lp = z - d.row_lse[r];
+    }
     d.seq_tokens[(size_t)sidx * d.tok_stride + P + g] = tok;
     d.seq_logp[(size_t)sidx * d.cap + g] = lp;
     ++g;
@@ -348,7 +371,7 @@ __global__ __launch_bounds__(1024) void k_sched_emit(SchedDev d) {
   __syncthreads();
   const int n_pre_step = d.status[STAT_NPRE_STEP];
   const int n_adm = n_pre;
-  rebuild_rows_and_status(d, sh, n_rows, n_fin, n_pre_step, n_adm);
+  rebuild_rows_and_status(d, sh, grp_of, n_rows, n_fin, n_pre_step, n_adm);
   if (t == 0) d.status[STAT_STEP] = step;
 }
 
@@ -399,7 +422,7 @@ __global__ __launch_bounds__(1024) void k_sched_boundary(SchedDev d, int n_group
     else d.ctr[CT_STALE] += n_out;
   }
   __syncthreads();
-  rebuild_rows_and_status(d, sh, 0, 0, 0, 0);
+  rebuild_rows_and_status(d, sh, grp_of, 0, 0, 0, 0);
 }
 
 // Feed prompts: one block per new sequence copies its record and prompt; the last step appends to the queue.
