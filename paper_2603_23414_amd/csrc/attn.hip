@@ -241,22 +241,48 @@ __global__ __launch_bounds__(64 * ATTN_GROUP) void k_decode_attn(
   // work item of group c: the row's full groups are consecutive from ws.x, a last shorter group sits at ws.y
   const int2 ws = row_wstart[row];
   const int nfull = ctx / (ATTN_GROUP * chunk_tokens);
+  // One wavefront per head.  The partials live at the memory side (uncached loads, a microsecond or two each), so
+  // they are fetched in batches: lane c takes the (max, sum) pair of group c in one round trip, the accumulators come
+  // eight groups at a time.  The order of every sum is fixed (butterfly over lanes, then ascending groups).
   for (int h = w; h < G; h += ATTN_GROUP) {
     const int head = kvh * G + h;
     float mx = NEG_BIG;
-    for (int c = 0; c < ngroups; ++c)
-      mx = fmaxf(mx, ld_agent(&part_ml[((size_t)(c < nfull ? ws.x + c : ws.y) * Hq + head) * 2]));
+    for (int c0 = 0; c0 < ngroups; c0 += 64) {
+      const int c = c0 + lane;
+      const float mc = c < ngroups ? ld_agent(&part_ml[((size_t)(c < nfull ? ws.x + c : ws.y) * Hq + head) * 2]) : NEG_BIG;
+      mx = fmaxf(mx, wave_max(mc));
+    }
     float den = 0.f, num[DPL];
 #pragma unroll
     for (int dd = 0; dd < DPL; ++dd) num[dd] = 0.f;
-    for (int c = 0; c < ngroups; ++c) {           // fixed order: group 0, 1, ..
-      const size_t pi = (size_t)(c < nfull ? ws.x + c : ws.y) * Hq + head;
-      const float wgt = __builtin_amdgcn_exp2f(ld_agent(&part_ml[pi * 2]) - mx);
-      den += wgt * ld_agent(&part_ml[pi * 2 + 1]);
+    for (int c0 = 0; c0 < ngroups; c0 += 64) {
+      const int c = c0 + lane;
+      float wgt = 0.f, lc = 0.f;
+      if (c < ngroups) {
+        const size_t pi = (size_t)(c < nfull ? ws.x + c : ws.y) * Hq + head;
+        wgt = __builtin_amdgcn_exp2f(ld_agent(&part_ml[pi * 2]) - mx);
+        lc = ld_agent(&part_ml[pi * 2 + 1]);
+      }
+      den += wave_sum(wgt * lc);
+      const int nb = min(64, ngroups - c0);
+      for (int u0 = 0; u0 < nb; u0 += 8) {
+        float v[8][DPL];
 #pragma unroll
-      for (int dd = 0; dd < DPL; ++dd) {
-        const int dim = lane + dd * 64;
-        if (D >= 64 || dim < D) num[dd] += wgt * ld_agent(&part_acc[pi * D + dim]);
+        for (int u = 0; u < 8; ++u) {
+          const int cu = c0 + min(u0 + u, nb - 1);          // past the end: the last group again, with weight zero
+          const size_t pi = (size_t)(cu < nfull ? ws.x + cu : ws.y) * Hq + head;
+#pragma unroll
+          for (int dd = 0; dd < DPL; ++dd) {
+            const int dim = lane + dd * 64;
+            v[u][dd] = (D >= 64 || dim < D) ? ld_agent(&part_acc[pi * D + dim]) : 0.f;
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const float wu = u0 + u < nb ? __shfl(wgt, u0 + u, 64) : 0.f;
+#pragma unroll
+          for (int dd = 0; dd < DPL; ++dd) num[dd] += wu * v[u][dd];
+        }
       }
     }
 #pragma unroll

@@ -14,7 +14,9 @@
 #ifndef ATTN_GROUP_CHUNKS
 #define ATTN_GROUP_CHUNKS 4
 #endif
+#ifndef ATTN_CHUNK_MIN
 #define ATTN_CHUNK_MIN 128
+#endif
 #define ATTN_CHUNK_MAX 1024         // 64 pages: their ids fit one register across a wavefront
 #ifndef ATTN_TARGET_ITEMS
 #define ATTN_TARGET_ITEMS 12288     // 256 CUs x 4 SIMDs x 3 resident waves x 4 rounds
