@@ -200,3 +200,32 @@ def test_argmax_ties_take_the_lowest_index(vocab, partner):
         assert decided >= 2 * n - 4
     finally:
         R.rollout_destroy(ctx)
+
+
+def test_harvest_larger_than_the_staging_buffers_goes_out_in_batches():
+    """600 rollouts of 7000 tokens each (4.2 M tokens) harvested in one call: more than the library's packed staging
+    buffers hold (2^22 elements), so the gather runs in several batches; every trajectory must land at its offset."""
+    import paper_2603_23414_amd as R
+    shape = W.ModelShape(1, 64, 2, 2, 32, 64, 64, 1e-5, 1e4, 0)
+    n, Lg = 600, 7000
+    ctx = make_engine(shape, None, max_slots=n, max_prompt_len=4, cap=Lg, max_seqs=n, debug_flags=R.ROLLOUT_DEBUG_NO_MODEL)
+    try:
+        prompts = [np.full(3, 1, np.int32)] * n
+        toks, offs = flat_prompts(prompts)
+        L = (Lg - np.arange(n) % 7).astype(np.uint32)          # lengths 6994..7000
+        R.rollout_submit(ctx, toks, offs, L)
+        for _ in range(Lg):
+            i = R.rollout_step(ctx)
+        assert i.n_active == 0 and i.n_finished_unharvested == n
+        ng, recs, tk, lp = R.rollout_harvest(ctx, n, R.ROLLOUT_FLUSH)
+        assert ng == 1 and len(recs) == n and len(tk) == int(L.sum()) > 1 << 22
+        off = 0
+        for r in recs:
+            assert r.tok_off == off and r.gen_len == L[r.seq_id]
+            seg = tk[off:off + r.gen_len]
+            assert seg[-1] == shape.vocab - 1 and not seg[:-1].any()        # scheduler-only tokens: zeros, then the forced EOS
+            off += r.gen_len
+        assert [r.gen_len for r in recs] == sorted(r.gen_len for r in recs)   # length-ordered
+        assert not lp.any()
+    finally:
+        R.rollout_destroy(ctx)

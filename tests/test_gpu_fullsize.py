@@ -98,9 +98,9 @@ def test_scheduler_bit_exact_at_full_scale(name):
         R.rollout_destroy(ctx)
 
 
-@pytest.mark.parametrize("name,layers", [("8b", 1), ("32b", 1), ("8b", 2), ("32b", 2)])
+@pytest.mark.parametrize("name,layers", [("8b", 1), ("32b", 1), ("8b", 2), ("32b", 2), ("8b", 4)])
 def test_slices_at_full_widths_teacher_forced(name, layers):
-    """One and two layers of the real widths (d_model, heads, FFN, full vocabulary): a few rollouts with 17-70 token
+    """One, two and four layers of the real widths (d_model, heads, FFN, full vocabulary): a few rollouts with 17-70 token
     prompts under teacher forcing.  The bar is the one of the 128-wide parity gate carried over by the logit scale
     (LOGIT_REL_TOL of the oracle logits' standard deviation); the absolute and the relative error are printed per
     depth."""
