@@ -372,20 +372,30 @@ void launch_write_kv(void* pool, int Hkv, int head_dim, const void* k, const voi
 // which keeps the online-softmax statistics, the rescaling and the final 1/l entirely lane-local.
 struct PfTile { int row0, n, slot, pos0; };
 
+// PF_KSPLIT wavefronts share one (query tile, head): wavefront w takes key tiles w, w + PF_KSPLIT, ..  A query tile deep
+// in a long sequence has hundreds of key tiles (512 at 16k tokens) and a wavefront walks its tiles one after the other, so
+// with one wavefront per query tile the launch lasted as long as its longest query tile while most of the chip had run
+// out of work -- that, not the softmax arithmetic or the K/V traffic, is what held the kernel at a tenth of the matrix
+// peak (a variant that shared K/V tiles between the heads of a group through a three-stage LDS ring was no faster).
+// The partial results of the wavefronts are merged pairwise through LDS in a fixed order (log-sum-exp merge).
+#define PF_KSPLIT 4
 template <int D>
-__global__ __launch_bounds__(64) void k_prefill_attn(const uint8_t* __restrict__ pool, const uint16_t* __restrict__ q,
-                                                     const PfTile* __restrict__ tiles, const int* __restrict__ page_table,
-                                                     int max_pages, int Hq, int Hkv, int G, uint16_t* __restrict__ out,
-                                                     float scale_log2e) {
+__global__ __launch_bounds__(64 * PF_KSPLIT, 2) void k_prefill_attn(const uint8_t* __restrict__ pool, const uint16_t* __restrict__ q,
+                                                                const PfTile* __restrict__ tiles,
+                                                                const int* __restrict__ page_table, int max_pages, int Hq,
+                                                                int Hkv, int G, uint16_t* __restrict__ out, float scale_log2e) {
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
   typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
   constexpr int KBYTES = PAGE_TOKENS * D * 2;
   constexpr int BLK = 2 * KBYTES;
   constexpr int NDC = D / 16;   // k-steps of the score product
   constexpr int NMT = D / 32;   // 32-dim tiles of the output
+  constexpr int MREC = NMT * 16 + 2;   // floats one lane hands over in a merge: its accumulators, m and l
+  __shared__ float mrg[2][MREC][64];   // [sender][value][lane]: lane-contiguous, conflict-free
   const PfTile tile = tiles[blockIdx.x];
   const int head = blockIdx.y, kvh = head / G;
-  const int lane = threadIdx.x, g = lane >> 5, c = lane & 31;
+  const int lane = threadIdx.x & 63, g = lane >> 5, c = lane & 31;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int row = tile.row0 + min(c, tile.n - 1);
   const int pos_c = tile.pos0 + c;
   const int last_key = tile.pos0 + tile.n - 1;
@@ -406,48 +416,49 @@ __global__ __launch_bounds__(64) void k_prefill_attn(const uint8_t* __restrict__
   float m_run = NEG_BIG, l_run = 0.f;
 
   const int n_kt = (last_key >> 5) + 1;
-  // software pipeline: the K fragments and the page id of key tile kt+1 and the V fragments of tile kt are all in
-  // flight while tile kt's scores are computed (a wave per workgroup has nothing else to hide those latencies with)
-  int pg = pt[min(c >> 4, last_page)];
-  u32x4 kf_next[NDC];
-  {
-    const uint8_t* kb = pool + ((size_t)pg * Hkv + kvh) * BLK + (c & 15) * 16 + g * 256;
-#pragma unroll
-    for (int dc = 0; dc < NDC; ++dc) kf_next[dc] = *(const u32x4*)(kb + dc * 512);
-  }
-  for (int kt = 0; kt < n_kt; ++kt) {
-    u32x4 kf[NDC];
-#pragma unroll
-    for (int dc = 0; dc < NDC; ++dc) kf[dc] = kf_next[dc];
-    const int pg_cur = pg;
-    // V fragments of this tile (both pages; a page wholly past the tile's last query is skipped below, its loads are
-    // clamped to the last valid page so they stay inside the slot's pages)
-    u32x4 vw[2][NMT];
+  // software pipeline: the K fragments of this wavefront's next key tile are fetched as soon as the score product has
+  // consumed the current ones, the V fragments as soon as the value product has
+  int pg = 0;
+  u32x4 kf[NDC], vw[2][NMT];
+  // V fragments of key tile `t` (both pages; a page wholly past the tile's last query is skipped in the product, its
+  // loads are clamped to the last valid page so they stay inside the slot's pages); pg_t holds the two page ids in
+  // lanes 0 and 16
+  auto load_v = [&](int pg_t, u32x4 (&v)[2][NMT]) {
 #pragma unroll
     for (int s2 = 0; s2 < 2; ++s2) {
-      const int pgs = __builtin_amdgcn_readlane(pg_cur, s2 * 16);
+      const int pgs = __builtin_amdgcn_readlane(pg_t, s2 * 16);
       const uint8_t* vb = pool + ((size_t)pgs * Hkv + kvh) * BLK + KBYTES + g * 8;
 #pragma unroll
       for (int mt = 0; mt < NMT; ++mt) {
         const int dim = mt * 32 + c;
         const u32x2 lo = *(const u32x2*)(vb + (size_t)dim * 16);
         const u32x2 hi = *(const u32x2*)(vb + (size_t)(D + dim) * 16);
-        vw[s2][mt].x = lo.x; vw[s2][mt].y = lo.y; vw[s2][mt].z = hi.x; vw[s2][mt].w = hi.y;
+        v[s2][mt].x = lo.x; v[s2][mt].y = lo.y; v[s2][mt].z = hi.x; v[s2][mt].w = hi.y;
       }
     }
-    {
-      const int kn = min(kt + 1, n_kt - 1) * 32 + c;         // past the end: the last tile once more
-      pg = pt[min(kn >> 4, last_page)];
-      const uint8_t* kb = pool + ((size_t)pg * Hkv + kvh) * BLK + (kn & 15) * 16 + g * 256;
+  };
+  if (w < n_kt) {                                          // uniform
+    pg = pt[min(w * 2 + (c >> 4), last_page)];
+    const uint8_t* kb = pool + ((size_t)pg * Hkv + kvh) * BLK + (c & 15) * 16 + g * 256;
 #pragma unroll
-      for (int dc = 0; dc < NDC; ++dc) kf_next[dc] = *(const u32x4*)(kb + dc * 512);
-    }
+    for (int dc = 0; dc < NDC; ++dc) kf[dc] = *(const u32x4*)(kb + dc * 512);
+    load_v(pg, vw);
+  }
+  for (int kt = w; kt < n_kt; kt += PF_KSPLIT) {
+    const int ktn = kt + PF_KSPLIT < n_kt ? kt + PF_KSPLIT : kt;   // past the end: this tile once more
+    const int kn = ktn * 32 + c;
+    pg = pt[min(kn >> 4, last_page)];                               // (its latency hides behind the score MFMAs)
     f32x16_t s;
 #pragma unroll
     for (int j = 0; j < 16; ++j) s[j] = 0.f;
 #pragma unroll
     for (int dc = 0; dc < NDC; ++dc)
       s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[dc]), qf[dc], s, 0, 0, 0);
+    {   // the next tile's K fragments go into the registers the score product has just consumed
+      const uint8_t* kb = pool + ((size_t)pg * Hkv + kvh) * BLK + (kn & 15) * 16 + g * 256;
+#pragma unroll
+      for (int dc = 0; dc < NDC; ++dc) kf[dc] = *(const u32x4*)(kb + dc * 512);
+    }
     // s[j] = score of key kt*32 + (j/4)*8 + g*4 + j%4 against this lane's query row.  Only key tiles that reach past
     // the tile's first query need the causal mask (the last one or two); the others are wholly visible.
     const bool diag = kt * 32 + 31 > tile.pos0;           // wave-uniform
@@ -468,8 +479,12 @@ __global__ __launch_bounds__(64) void k_prefill_attn(const uint8_t* __restrict__
     }
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m_run, mx);
-    // the running maximum rarely moves after the first tiles: rescale the accumulators only when some row's did
-    if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
+    // Rescaling the accumulators is 64 multiplies per lane, and with 64 rows-halves in a wavefront SOME row's maximum
+    // moves in most tiles until a few thousand keys have been seen.  The running maximum is therefore only a reference
+    // point: it is moved (and the accumulators rescaled) when some row's scores exceed it by more than 2^8; until then
+    // probabilities up to 256 are accumulated against the old reference, which fp32 sums and bf16 operands (relative
+    // precision) take without loss, and the final division by l cancels the reference exactly.
+    if (__builtin_amdgcn_ballot_w64(m_new > m_run + 8.0f) != 0) {
       const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
       l_run *= alpha;
 #pragma unroll
@@ -478,14 +493,15 @@ __global__ __launch_bounds__(64) void k_prefill_attn(const uint8_t* __restrict__
         for (int j = 0; j < 16; ++j) o[mt][j] *= alpha;
       m_run = m_new;
     }
+    // a row whose keys in this wavefront's tiles are all masked so far still has m_run = -1e30: subtract a floor
+    // instead, so that exp2 of a masked score underflows to exactly 0 whatever m_run is
+    const float m_sub = fmaxf(m_run, -1.0e20f);
     float ls = 0.f;
     uint32_t pk[8];
 #pragma unroll
     for (int j = 0; j < 16; j += 2) {
-      // exp2 of a masked score (-1e30 - m) underflows to exactly 0; key 0 is visible to every valid row, so m_run is
-      // a real score from the first tile on
-      const float p0 = __builtin_amdgcn_exp2f(s[j] - m_run);
-      const float p1 = __builtin_amdgcn_exp2f(s[j + 1] - m_run);
+      const float p0 = __builtin_amdgcn_exp2f(s[j] - m_sub);
+      const float p1 = __builtin_amdgcn_exp2f(s[j + 1] - m_sub);
       ls += p0 + p1;
       pk[j >> 1] = pack_bf2(p0, p1);
     }
@@ -500,7 +516,40 @@ __global__ __launch_bounds__(64) void k_prefill_attn(const uint8_t* __restrict__
       for (int mt = 0; mt < NMT; ++mt)
         o[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vw[s2][mt]), pf, o[mt], 0, 0, 0);
     }
+    load_v(pg, vw);                                      // the next tile's V fragments, into the registers just consumed
   }
+
+  // ---- merge the wavefronts' partial results: 2 -> 0 and 3 -> 1, then 1 -> 0 (lane-local: every wavefront keeps the
+  // same (query row, dims) in the same lane and register).  A wavefront without tiles hands over weight zero.
+  auto send = [&](int slot) {
+#pragma unroll
+    for (int mt = 0; mt < NMT; ++mt)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) mrg[slot][mt * 16 + j][lane] = o[mt][j];
+    mrg[slot][NMT * 16][lane] = m_run;
+    mrg[slot][NMT * 16 + 1][lane] = l_run;
+  };
+  auto take = [&](int slot) {
+    const float mb = mrg[slot][NMT * 16][lane], lb = mrg[slot][NMT * 16 + 1][lane];
+    const float M = fmaxf(m_run, mb);
+    const float wa = __builtin_amdgcn_exp2f(m_run - M), wb = __builtin_amdgcn_exp2f(mb - M);
+    l_run = l_run * wa + lb * wb;
+    m_run = M;
+#pragma unroll
+    for (int mt = 0; mt < NMT; ++mt)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) o[mt][j] = o[mt][j] * wa + mrg[slot][mt * 16 + j][lane] * wb;
+  };
+  static_assert(PF_KSPLIT == 4, "the merge below is written for four wavefronts");
+  if (w >= 2) send(w - 2);
+  __syncthreads();
+  if (w < 2) take(w);
+  __syncthreads();
+  if (w == 1) send(0);
+  __syncthreads();
+  if (w != 0) return;
+  take(0);
+
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   if (c < tile.n) {
     const float inv = 1.f / l_tot;
@@ -524,9 +573,9 @@ void launch_prefill_attn(const void* pool, const void* q, const void* tiles, int
   const float scale = 1.4426950408889634f / sqrtf((float)head_dim);
   dim3 grid(n_tiles, Hq);
   if (head_dim == 128)
-    hipLaunchKernelGGL((k_prefill_attn<128>), grid, dim3(64), 0, st, (const uint8_t*)pool, (const uint16_t*)q,
+    hipLaunchKernelGGL((k_prefill_attn<128>), grid, dim3(64 * PF_KSPLIT), 0, st, (const uint8_t*)pool, (const uint16_t*)q,
                        (const PfTile*)tiles, page_table, max_pages, Hq, Hkv, Hq / Hkv, (uint16_t*)out, scale);
   else
-    hipLaunchKernelGGL((k_prefill_attn<32>), grid, dim3(64), 0, st, (const uint8_t*)pool, (const uint16_t*)q,
+    hipLaunchKernelGGL((k_prefill_attn<32>), grid, dim3(64 * PF_KSPLIT), 0, st, (const uint8_t*)pool, (const uint16_t*)q,
                        (const PfTile*)tiles, page_table, max_pages, Hq, Hkv, Hq / Hkv, (uint16_t*)out, scale);
 }
