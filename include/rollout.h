@@ -254,9 +254,11 @@ int rollout_gemm_bf16(const void* a_dev, const void* w_packed_dev, float* c_dev,
  * same result bit for bit.  The split-K partial sums go to a fixed array of rollout_gemm_static_scratch_bytes()
  * (32 MiB) inside the library's device image; every GPU the library runs on holds its own copy until the process
  * ends.  The call runs on the current device, allocates nothing (no hipMalloc / hipFree, no allocating library
- * routine) and only enqueues on `stream`.  Errors: EINVAL as rollout_gemm_bf16; ERANGE when
- * rollout_gemm_splits(M, N, K) * M * N * 4 bytes exceed the array (shapes with one split need no scratch and are never
- * refused: all decode projections of the 8B and 32B shapes at their batch sizes fit); EDEVICE.  All calls on one GPU
+ * routine) and only enqueues on `stream`.  Errors: EINVAL as rollout_gemm_bf16 (K not a multiple of 64, a dimension
+ * beyond the maxima above); ERANGE when rollout_gemm_splits(M, N, K) * M * N * 4 bytes exceed the array -- a second line
+ * of defence: the library never launches more than 256 workgroups of a split-K product (splits x 128-column tiles x
+ * 256-row blocks), which bounds the partial sums of every shape by 256 x 256 x 128 fp32 = the array's 32 MiB (the O
+ * projection of the 8B shape at 256 rows, 8 splits, fills it exactly); EDEVICE.  All calls on one GPU
  * share that GPU's array, which keeps the last call's contents (every split overwrites its whole partial, nothing
  * needs clearing): calls that overlap on one GPU -- different streams or threads -- race, so serialise them. */
 uint64_t rollout_gemm_static_scratch_bytes(void);

@@ -12,7 +12,8 @@
 //   V block [2][d][8 tokens]          -> value phase, one lane per output dim, tokens paired for dot2
 // Scores and values use v_dot2c_f32_bf16 with the query held in scalar registers; probabilities go
 // through a 512-byte per-wave LDS tile (bf16) to be re-read as broadcast operands.  Softmax statistics
-// and accumulators are fp32.  Chunk groups of one row are merged by k_attn_merge (log-sum-exp merge).
+// and accumulators are fp32.  The chunk groups of one (row, kv head) are merged inside the kernel by whichever of them
+// arrives last (log-sum-exp merge in group order).
 #include "common.h"
 #include "kernels.h"
 

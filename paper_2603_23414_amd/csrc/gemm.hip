@@ -10,6 +10,7 @@
 // blockIdx.z writes fp32 partial sums that the consumer kernels (residual+norm, RoPE, SiLU*mul) add up in a
 // fixed order, so results are deterministic.
 #include <cstdio>
+#include <cstdlib>
 
 #include "common.h"
 #include "kernels.h"
@@ -28,6 +29,15 @@ template <bool STREAM>
 __device__ __forceinline__ u32x4 ldw(const uint16_t* p) {
   return STREAM ? __builtin_nontemporal_load((const u32x4*)p) : *(const u32x4*)p;
 }
+#ifndef GEMM_STAGE_MI1      // k blocks per activation stage of k_gemm_bf16 at 32 / 64 / 128 rows
+#define GEMM_STAGE_MI1 4
+#endif
+#ifndef GEMM_STAGE_MI2
+#define GEMM_STAGE_MI2 2
+#endif
+#ifndef GEMM_STAGE_MI4
+#define GEMM_STAGE_MI4 2
+#endif
 #define LDS_ROW 72   // bf16 elements per LDS row: 64 + 8 padding (144-byte stride: conflict-free 16-byte reads)
 
 // One k-step pairs MFMA k index (lane/32)*8 + e with memory k = (lane/32)*32 + j*8 + e inside the 64-wide block,
@@ -49,7 +59,14 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16(const uint16_t* __restrict
                                                       float* __restrict__ C, int M, int N, int K, int kb_per_split,
                                                       LmEpi lm) {
   constexpr int BM = 32 * MI;
-  __shared__ __align__(16) uint16_t a_lds[2][BM * LDS_ROW];
+  // The activation tile is staged SB k blocks at a time (global -> registers -> LDS, double-buffered), so the wait for
+  // its loads and the workgroup barrier come once per SB blocks.  With one block per stage every iteration of a
+  // small-M launch lasted one L2 round trip (0.7 us for 16 KiB of weights per workgroup): that chain, not the weight
+  // stream, set the speed of the decode projections at M <= 128.  The W ring's depth is a multiple of SB so that a
+  // block's position inside its stage is a compile-time constant.
+  constexpr int SB = MI == 1 ? GEMM_STAGE_MI1 : MI == 2 ? GEMM_STAGE_MI2 : MI == 4 ? GEMM_STAGE_MI4 : 1;
+  constexpr int RD = SB == 1 ? 3 : (SB == 2 ? 4 : SB);
+  __shared__ __align__(16) uint16_t a_lds[2][SB][BM * LDS_ROW];
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n_base = blockIdx.x * 128 + w * 32;
@@ -59,16 +76,31 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16(const uint16_t* __restrict
   const int nkb = min(kb_per_split, nkb_total - kb0);
   float* __restrict__ Cz = C + (size_t)blockIdx.z * M * N;
 
-  const int nt = min(n_base, N - 1) >> 5;                      // this wave's 32-row weight tile (clamped past the edge)
-  const uint16_t* __restrict__ wrow = W + ((size_t)nt * nkb_total + kb0) * WTILE_ELEMS + lane * 8;
+  // Operands are fetched with buffer loads: this row block of A and this wave's tile row of W (32 rows, clamped past the
+  // edge: loaded, never stored) each get a descriptor, every offset used below stays inside it, and a prefetch that would
+  // reach past the launch's last k block is issued against an EMPTY descriptor instead (zero records: the range check
+  // returns zeros without touching memory, and the load still counts in the wave's load counter) -- the loop keeps its
+  // fixed shape with no conditional register writes, and a short split-K range does not fetch its last block three
+  // times over.
+  const int nt = min(n_base, N - 1) >> 5;
+  const int rows_here = min(BM, M - m_base);
+  const uint16_t* a_base = A + (size_t)m_base * K;
+  const uint16_t* w_base = W + (size_t)nt * nkb_total * WTILE_ELEMS;
+  const int a_bytes = rows_here * K * 2, w_bytes = nkb_total * (WTILE_ELEMS * 2);
+#define GEMM_RS_A(live) __builtin_amdgcn_make_buffer_rsrc((void*)a_base, 0, (live) ? a_bytes : 0, 0x00020000)
+#define GEMM_RS_W(live) __builtin_amdgcn_make_buffer_rsrc((void*)w_base, 0, (live) ? w_bytes : 0, 0x00020000)
+#define GEMM_LDW(rs, kb_, j) \
+  __builtin_amdgcn_raw_buffer_load_b128(rs, w_voff + (j) * 1024, (kb0 + (kb_)) * (WTILE_ELEMS * 2), STREAM ? 2 : 0)
+#define GEMM_LDA(rs, i, kb_) __builtin_amdgcn_raw_buffer_load_b128(rs, a_voff[i], (kb0 + (kb_)) * (GEMM_BK * 2), 0)
+  const int w_voff = lane * 16;
 
   const int a_col = tid & 7;
-  const uint16_t* a_src[MI];
+  int a_voff[MI];
   int a_dst[MI];
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
     const int r = (tid >> 3) + i * 32;
-    a_src[i] = A + (size_t)min(m_base + r, M - 1) * K + (size_t)kb0 * GEMM_BK + a_col * 8;
+    a_voff[i] = min(r, rows_here - 1) * K * 2 + a_col * 16;    // rows past M: the last row again (computed, never stored)
     a_dst[i] = r * LDS_ROW + a_col * 8;
   }
   const int a_frag = (lane & 31) * LDS_ROW + (lane >> 5) * 32;
@@ -79,36 +111,50 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16(const uint16_t* __restrict
 #pragma unroll
     for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
 
-  u32x4 breg[3][4];   // ring over k blocks; every index below is a compile-time constant after unrolling
-  u32x4 areg[MI];
+  u32x4 breg[RD][4];   // ring over k blocks; every index below is a compile-time constant after unrolling
+  u32x4 areg[SB][MI];
 #pragma unroll
-  for (int i = 0; i < MI; ++i) areg[i] = *(const u32x4*)(a_src[i]);
+  for (int s = 0; s < SB; ++s) {
+    const __amdgpu_buffer_rsrc_t rs = GEMM_RS_A(s < nkb);
 #pragma unroll
-  for (int j = 0; j < 4; ++j) breg[0][j] = ldw<STREAM>(wrow + j * 512);
-  {
-    const size_t w1 = (size_t)min(1, nkb - 1) * WTILE_ELEMS;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) breg[1][j] = ldw<STREAM>(wrow + w1 + j * 512);
+    for (int i = 0; i < MI; ++i) areg[s][i] = GEMM_LDA(rs, i, min(s, nkb - 1));
   }
 #pragma unroll
-  for (int i = 0; i < MI; ++i) *(u32x4*)&a_lds[0][a_dst[i]] = areg[i];
+  for (int r = 0; r < RD - 1; ++r) {
+    const __amdgpu_buffer_rsrc_t rs = GEMM_RS_W(r < nkb);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) breg[r][j] = GEMM_LDW(rs, min(r, nkb - 1), j);
+  }
+#pragma unroll
+  for (int s = 0; s < SB; ++s)
+#pragma unroll
+    for (int i = 0; i < MI; ++i) *(u32x4*)&a_lds[0][s][a_dst[i]] = areg[s][i];
   __syncthreads();
 
-  for (int kbase = 0; kbase < nkb; kbase += 3) {
+  for (int kbase = 0; kbase < nkb; kbase += RD) {
 #pragma unroll
-    for (int u = 0; u < 3; ++u) {
+    for (int u = 0; u < RD; ++u) {
       const int kb = kbase + u;
       if (kb < nkb) {                                    // uniform
-        const int cur = kb & 1;
-        // prefetch: A one block ahead (to registers, then LDS), W two blocks ahead (register ring).  Past the
-        // end the last block is simply loaded again, which keeps the loop free of conditional register writes.
-        const size_t k1 = (size_t)min(kb + 1, nkb - 1) * GEMM_BK, w2 = (size_t)min(kb + 2, nkb - 1) * WTILE_ELEMS;
+        const int pos = u % SB;                          // a constant once unrolled: kbase is a multiple of RD, RD of SB
+        const int cur = (kb / SB) & 1;
+        // prefetch: the next stage of A at the first block of a stage (to registers, then LDS), W RD - 1 blocks ahead
+        // (register ring); past the launch's last block the loads go against the empty descriptor
+        if (pos == 0) {
 #pragma unroll
-        for (int i = 0; i < MI; ++i) areg[i] = *(const u32x4*)(a_src[i] + k1);
+          for (int s = 0; s < SB; ++s) {
+            const __amdgpu_buffer_rsrc_t rs = GEMM_RS_A(kb + SB + s < nkb);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) breg[(u + 2) % 3][j] = ldw<STREAM>(wrow + w2 + j * 512);
+            for (int i = 0; i < MI; ++i) areg[s][i] = GEMM_LDA(rs, i, min(kb + SB + s, nkb - 1));
+          }
+        }
+        {
+          const __amdgpu_buffer_rsrc_t rs = GEMM_RS_W(kb + RD - 1 < nkb);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) breg[(u + RD - 1) % RD][j] = GEMM_LDW(rs, min(kb + RD - 1, nkb - 1), j);
+        }
         __builtin_amdgcn_sched_barrier(0);   // keep the prefetch loads ahead of this block's MFMAs
-        const uint16_t* al = a_lds[cur] + a_frag;
+        const uint16_t* al = a_lds[cur][pos] + a_frag;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const bf16x8_t bf = __builtin_bit_cast(bf16x8_t, breg[u][j]);
@@ -119,17 +165,26 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16(const uint16_t* __restrict
             else acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av), bf, acc[i], 0, 0, 0);
           }
         }
+        if (pos == SB - 1) {                             // the stage is used up: publish the next one
 #pragma unroll
-        for (int i = 0; i < MI; ++i) *(u32x4*)&a_lds[cur ^ 1][a_dst[i]] = areg[i];
-        __syncthreads();
+          for (int s = 0; s < SB; ++s)
+#pragma unroll
+            for (int i = 0; i < MI; ++i) *(u32x4*)&a_lds[cur ^ 1][s][a_dst[i]] = areg[s][i];
+          __syncthreads();
+        }
       }
     }
   }
 
+#undef GEMM_LDA
+#undef GEMM_LDW
+#undef GEMM_RS_W
+#undef GEMM_RS_A
   if (EPI >= 2) {
     constexpr bool SAMPLING = EPI == 3;                   // a separate instantiation: the generator is 128 x inlined
     // transposed tile: element j of lane -> column n_base + (j/4)*8 + (lane/32)*4 + j%4 (ascending in j), row lane%32
-    float* rec_f = (float*)&a_lds[0][0];                  // [4 waves][BM rows][4]; the A tiles are dead (last barrier passed)
+    if (SB > 1) __syncthreads();                          // a launch may end in the middle of a stage: no wave still reads A
+    float* rec_f = (float*)&a_lds[0][0][0];               // [4 waves][BM rows][4]; the A tiles are dead (last barrier passed)
     int* rec_i = (int*)(rec_f + 4 * BM * 4);              // [4 waves][BM rows]
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
@@ -254,11 +309,15 @@ __global__ __launch_bounds__(256, 1) void k_gemm_bf16_deep(const uint16_t* __res
   float* __restrict__ Cz = C + (size_t)blockIdx.z * M * N;
   // buffer descriptors: this row block of A, this wave's tile row of W (32 rows, clamped past the edge: loaded, never
   // stored).  Every offset below stays inside them; the hardware range check is only a second line of defence.
+  // A prefetch that would reach past the launch's last k block goes against an EMPTY descriptor (zero records: the range
+  // check answers with zeros and no memory access, and the load still counts in the wave's load counter), so the loop keeps
+  // its fixed shape and its hand-counted waits while a short split-K range does not fetch its last block four times.
   const int rows_here = min(256, M - m_base);
-  const __amdgpu_buffer_rsrc_t a_rs =
-      __builtin_amdgcn_make_buffer_rsrc((void*)(A + (size_t)m_base * K), 0, rows_here * K * 2, 0x00020000);
-  const __amdgpu_buffer_rsrc_t w_rs = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)(W + (size_t)(min(n_base, N - 1) >> 5) * nkb_total * WTILE_ELEMS), 0, nkb_total * (WTILE_ELEMS * 2), 0x00020000);
+  const uint16_t* a_base = A + (size_t)m_base * K;
+  const uint16_t* w_base = W + (size_t)(min(n_base, N - 1) >> 5) * nkb_total * WTILE_ELEMS;
+  const int a_bytes = rows_here * K * 2, w_bytes = nkb_total * (WTILE_ELEMS * 2);
+#define DEEP_RS_A(live) __builtin_amdgcn_make_buffer_rsrc((void*)a_base, 0, (live) ? a_bytes : 0, 0x00020000)
+#define DEEP_RS_W(live) __builtin_amdgcn_make_buffer_rsrc((void*)w_base, 0, (live) ? w_bytes : 0, 0x00020000)
   const int w_so = kb0 * (WTILE_ELEMS * 2);
   const int w_voff = lane * 16;
   // A load i of wave w fills tile rows i*32 + w*8 .. +8: lane -> row l/8, physical chunk l%8 <- logical chunk
@@ -269,10 +328,10 @@ __global__ __launch_bounds__(256, 1) void k_gemm_bf16_deep(const uint16_t* __res
 #pragma unroll
   for (int i = 0; i < 8; ++i) a_voff[i] = min(i * 32 + lrow, rows_here - 1) * K * 2 + a_chunk;
   const int a_so = kb0 * (GEMM_BK * 2);
-#define DEEP_LDA(buf, i, kb_)                                                                                     \
-  __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rs, (lds_ptr_t)(DEEP_SEL(buf) + ((i) * 32 + w * 8) * 64), 16, a_voff[i], \
+#define DEEP_LDA(rs, buf, i, kb_)                                                                                \
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr_t)(DEEP_SEL(buf) + ((i) * 32 + w * 8) * 64), 16, a_voff[i], \
                                            a_so + (kb_) * (GEMM_BK * 2), 0, 0)
-#define DEEP_LDW(kb_, j) __builtin_amdgcn_raw_buffer_load_b128(w_rs, w_voff, w_so + (kb_) * (WTILE_ELEMS * 2) + (j) * 1024, 2)
+#define DEEP_LDW(rs, kb_, j) __builtin_amdgcn_raw_buffer_load_b128(rs, w_voff, w_so + (kb_) * (WTILE_ELEMS * 2) + (j) * 1024, 2)
 #define DEEP_MFMA8(AF, BF)                                                                                        \
   _Pragma("unroll") for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                  \
       __builtin_bit_cast(bf16x8_t, AF[i]), BF, acc[i], 0, 0, 0)
@@ -297,15 +356,19 @@ __global__ __launch_bounds__(256, 1) void k_gemm_bf16_deep(const uint16_t* __res
     for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
   u32x4 breg[4][4];   // W ring; every index is a compile-time constant after unrolling
   u32x4 af[2][8];     // A fragments of the current and the next k-step
-  // prologue: A blocks 0..2 into tiles 0..2, W blocks 0..2 (past the end the last block is simply loaded again)
+  // prologue: A blocks 0..2 into tiles 0..2, W blocks 0..2
 #pragma unroll
-  for (int b = 0; b < 3; ++b)
+  for (int b = 0; b < 3; ++b) {
+    const __amdgpu_buffer_rsrc_t rs = DEEP_RS_A(b < nkb);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) DEEP_LDA(b, i, min(b, nkb - 1));
+    for (int i = 0; i < 8; ++i) DEEP_LDA(rs, b, i, min(b, nkb - 1));
+  }
 #pragma unroll
-  for (int r = 0; r < 3; ++r)
+  for (int r = 0; r < 3; ++r) {
+    const __amdgpu_buffer_rsrc_t rs = DEEP_RS_W(r < nkb);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) breg[r][j] = DEEP_LDW(min(r, nkb - 1), j);
+    for (int j = 0; j < 4; ++j) breg[r][j] = DEEP_LDW(rs, min(r, nkb - 1), j);
+  }
   __builtin_amdgcn_s_waitcnt(0x0F70 | 12);   // vmcnt(12): the 24 A loads have landed, the 12 W loads may still fly
   __syncthreads();
 #pragma unroll
@@ -319,12 +382,13 @@ __global__ __launch_bounds__(256, 1) void k_gemm_bf16_deep(const uint16_t* __res
         const uint16_t* al = DEEP_SEL(u % 4);
         const uint16_t* al_next = DEEP_SEL((u + 1) % 4);
         const int k3 = min(kb + 3, nkb - 1);
+        const __amdgpu_buffer_rsrc_t a_rs3 = DEEP_RS_A(kb + 3 < nkb), w_rs3 = DEEP_RS_W(kb + 3 < nkb);
         // k-step 0: + A block kb+3 straight into tile (kb+3) % 4 (last read before the previous barrier)
 #pragma unroll
         for (int i = 0; i < 8; ++i) af[1][i] = *(const u32x4*)(al + a_frag[1] + i * 32 * 64);
         DEEP_MFMA8(af[0], __builtin_bit_cast(bf16x8_t, breg[u % 4][0]));
 #pragma unroll
-        for (int i = 0; i < 8; ++i) DEEP_LDA((u + 3) % 4, i, k3);
+        for (int i = 0; i < 8; ++i) DEEP_LDA(a_rs3, (u + 3) % 4, i, k3);
         DEEP_PIN(1)
         // k-step 1
 #pragma unroll
@@ -336,7 +400,7 @@ __global__ __launch_bounds__(256, 1) void k_gemm_bf16_deep(const uint16_t* __res
         for (int i = 0; i < 8; ++i) af[1][i] = *(const u32x4*)(al + a_frag[3] + i * 32 * 64);
         DEEP_MFMA8(af[0], __builtin_bit_cast(bf16x8_t, breg[u % 4][2]));
 #pragma unroll
-        for (int j = 0; j < 4; ++j) breg[(u + 3) % 4][j] = DEEP_LDW(k3, j);
+        for (int j = 0; j < 4; ++j) breg[(u + 3) % 4][j] = DEEP_LDW(w_rs3, k3, j);
         DEEP_PIN(2)
         // k-step 3: first fragments of block kb+1 (published one barrier ago)
 #pragma unroll
@@ -351,11 +415,13 @@ __global__ __launch_bounds__(256, 1) void k_gemm_bf16_deep(const uint16_t* __res
       }
     }
   }
-  __builtin_amdgcn_s_waitcnt(0x0F70);   // the redundant loads past the last block have landed before LDS is given up
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // the loads issued past the last block have completed before LDS is given up
 #undef DEEP_PIN
 #undef DEEP_MFMA8
 #undef DEEP_LDW
 #undef DEEP_LDA
+#undef DEEP_RS_W
+#undef DEEP_RS_A
 #undef DEEP_SEL
 
   // C fragment: element j of lane -> row (j/4)*8 + (lane/32)*4 + j%4, col lane%32
@@ -581,19 +647,22 @@ __global__ void k_reduce_splits(const float* __restrict__ part, float* __restric
 // Number of K splits: enough workgroups to cover the chip's 256 CUs without drowning the weight stream
 // in partial-sum traffic.
 int gemm_pick_splits(int M, int N, int K) {
+#ifdef GEMM_SPLIT_SWEEP
+  if (const char* e = getenv("GEMM_S")) { const int nkb_ = K / GEMM_BK, S_ = atoi(e); const int per_ = (nkb_ + S_ - 1) / S_; return (nkb_ + per_ - 1) / per_; }
+#endif
+  // Never more workgroups than the chip has CUs: a launch of 280-320 workgroups puts a second one on some CUs, which
+  // then set its length (QKV at 8-128 rows: 6 splits = 288 workgroups 15.9-29.4 us, 5 splits = 240 workgroups 13.4-25.5 us;
+  // the 32B shapes at 64 rows likewise).  At most 8 splits (partial-sum traffic), and with up to 128 rows at least 10 k
+  // blocks per split (O projection: 6 splits of 11 blocks beat 8 of 8).  splits x tiles <= 256 also bounds the partial
+  // sums of any shape by 256 x 256 x 128 fp32 = 32 MiB.
   const int mblocks = (M + 255) / 256;
   const int tiles = ((N + 127) / 128) * mblocks;
   const int nkb = K / GEMM_BK;
-  int S = 1;
-  if (tiles < 192) S = M > 128 ? 256 / tiles : (256 + tiles - 1) / tiles;   // M > 128: stay within one workgroup per CU (deep kernel)
+  int S = tiles < 192 ? 256 / tiles : 1;
   if (S > 8) S = 8;
-  // M <= 128 runs two workgroups per CU: with a deep K (>= 32 blocks left per split) fill both slots of every CU --
-  // 280-320 workgroups leave a quarter of the CUs with twice the work (32B down projection at M = 64: 69 -> 55 us)
-  if (tiles < 192 && M <= 128) {
-    const int S2 = (512 + tiles - 1) / tiles;
-    if (S2 > S && nkb / S2 >= 32) S = S2;
-  }
-  if (S > nkb / 4) S = nkb / 4 > 0 ? nkb / 4 : 1;
+  if (M <= 128 && S > nkb / 10) S = nkb / 10;
+  if (S > nkb / 4) S = nkb / 4;
+  if (S < 1) S = 1;
   const int per = (nkb + S - 1) / S;
   return (nkb + per - 1) / per;
 }

@@ -28,7 +28,7 @@ def _names(R, m, rows):
     # a ragged 130 rows: the 256-row kernels with clamped rows
     ("8b", 130, 2048, dict(qkv="k_gemm_bf16_deep<0>", o="k_gemm_bf16_deep<0>", gate_up="k_gemm_bf16_deep<1>",
                            down="k_gemm_bf16_deep<0>", lm_head="k_gemm_bf16_deep<0>")),
-    # the 32B batch: 64 rows, group of 5 query heads, QKV bias, 13-way split of the down projection
+    # the 32B batch: 64 rows, group of 5 query heads, QKV bias, 6-way split of the down projection
     ("32b", 64, 2048, dict(qkv="k_gemm_bf16<2,0,true>", o="k_gemm_bf16<2,0,true>", gate_up="k_gemm_bf16<2,1,true>",
                            down="k_gemm_bf16<2,0,true>", lm_head="k_gemm_bf16<2,0,true>")),
 ])
@@ -41,7 +41,7 @@ def test_full_batch_one_layer_slice_teacher_forced(name, Q, vocab, expect):
     m = dataclasses.replace(W.CONFIGS[name].model.with_layers(1), vocab=vocab)
     assert _names(R, m, Q) == expect
     if name == "32b":
-        assert R.rollout_gemm_splits(Q, m.d_model, m.d_ffn) == 13
+        assert R.rollout_gemm_splits(Q, m.d_model, m.d_ffn) == 6
     blob = W.make_weights(m, 11)
     g = W.rng(12)
     prompts = [g.integers(0, m.vocab - 1, int(k)).astype(np.int32) for k in g.integers(1, 3, Q)]
@@ -75,7 +75,7 @@ def _gemm_inputs(M, N, K, seed):
     (64, 152064, 5120, "k_gemm_bf16<2,0,true>"),     # the 32B LM head at its batch
     (256, 6144, 4096, "k_gemm_bf16_deep<0>"),        # 8B QKV, 5 splits
     (256, 4096, 14336, "k_gemm_bf16_deep<0>"),       # 8B down, 8 splits
-    (64, 5120, 27648, "k_gemm_bf16<2,0,true>"),      # 32B down, 13 splits
+    (64, 5120, 27648, "k_gemm_bf16<2,0,true>"),      # 32B down, 6 splits
 ])
 def test_projection_shapes_of_the_timed_step(M, N, K, kernel):
     import torch

@@ -62,23 +62,40 @@ def test_static_scratch_gemm_equals_the_workspace_gemm_on_two_calls_in_a_row():
     import torch
     import paper_2603_23414_amd as R
     assert R.rollout_gemm_static_scratch_bytes() == 32 << 20
-    assert R.rollout_gemm_splits(256, 4096, 4096) == 8 and R.rollout_gemm_splits(100, 640, 1024) > 1
+    assert R.rollout_gemm_splits(256, 4096, 4096) == 8 and R.rollout_gemm_splits(100, 640, 2560) > 1
     _run_both(R, torch, 256, 4096, 4096, 1)     # 8 splits x 256 x 4096 fp32 = the whole 32 MiB
-    _run_both(R, torch, 100, 640, 1024, 2)      # smaller, right after: the array still holds the first call's partials
+    _run_both(R, torch, 100, 640, 2560, 2)      # smaller, right after: the array still holds the first call's partials
     _run_both(R, torch, 64, 33024, 128, 3)      # one split: no scratch at all
 
 
+def test_static_scratch_holds_the_partial_sums_of_every_shape():
+    """The split rule never launches more workgroups than 256 (splits x column tiles x row blocks), so the partial sums
+    of any shape stay within 256 x 256 x 128 fp32 = the array's 32 MiB; the entry point's size check is a second line
+    of defence.  Host arithmetic only: no GPU needed."""
+    import paper_2603_23414_amd as R
+    cap = R.rollout_gemm_static_scratch_bytes()
+    g = W.rng(5)
+    worst = 0
+    shapes = [(256, 4096, 4096), (256, 4096, 14336), (128, 384, 1 << 19), (256, 384, 1 << 19), (8192, 128, 4096),
+              (64, 5120, 27648), (257, 2048, 8192), (4096, 384, 4096)]
+    shapes += [(int(g.integers(1, 9000)), int(g.integers(1, 30000)), 64 * int(g.integers(1, 600))) for _ in range(3000)]
+    for M, N, K in shapes:
+        S = R.rollout_gemm_splits(M, N, K)
+        assert 1 <= S <= 8
+        if S > 1:
+            worst = max(worst, S * M * N * 4)
+    assert 0 < worst <= cap
+    assert R.rollout_gemm_splits(256, 4096, 4096) * 256 * 4096 * 4 == cap       # the O projection at the headline batch fills it
+
+
 @gpu
-def test_static_scratch_gemm_rejects_what_does_not_fit():
+def test_static_scratch_gemm_rejects_bad_sizes():
     import torch
     import paper_2603_23414_amd as R
-    M, N, K = 128, 384, 1 << 19                 # a very deep, narrow product: 171 splits x 128 x 384 fp32 = 32.06 MiB
-    need = R.rollout_gemm_splits(M, N, K) * M * N * 4
-    assert need > R.rollout_gemm_static_scratch_bytes()
     t = torch.zeros(64, dtype=torch.int16, device="cuda:0")
     with pytest.raises(R.RolloutError) as e:
-        R.rollout_gemm_bf16_static(t.data_ptr(), t.data_ptr(), t.data_ptr(), M, N, K)
-    assert e.value.code == -4 and "static scratch" in str(e.value)
-    with pytest.raises(R.RolloutError) as e:
-        R.rollout_gemm_bf16_static(t.data_ptr(), t.data_ptr(), t.data_ptr(), 1, 32, 100)
+        R.rollout_gemm_bf16_static(t.data_ptr(), t.data_ptr(), t.data_ptr(), 1, 32, 100)          # K not a multiple of 64
     assert e.value.code == -1
+    with pytest.raises(R.RolloutError) as e:
+        R.rollout_gemm_bf16_static(t.data_ptr(), t.data_ptr(), t.data_ptr(), 8, 128, 1 << 21)      # beyond the stated maximum
+    assert e.value.code == -1 and "too large" in str(e.value)
