@@ -10,7 +10,7 @@
 // blockIdx.z writes fp32 partial sums that the consumer kernels (residual+norm, RoPE, SiLU*mul) add up in a
 // fixed order, so results are deterministic.
 #include <cstdio>
-#include <cstdlib>
+#include <type_traits>
 
 #include "common.h"
 #include "kernels.h"
@@ -131,47 +131,63 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16(const uint16_t* __restrict
     for (int i = 0; i < MI; ++i) *(u32x4*)&a_lds[0][s][a_dst[i]] = areg[s][i];
   __syncthreads();
 
-  for (int kbase = 0; kbase < nkb; kbase += RD) {
+  // one k block; u = kb % RD is a compile-time constant (ring slot, position inside the activation stage)
+  auto block = [&](auto uc, const int kb) __attribute__((always_inline)) {
+    constexpr int u = decltype(uc)::value;
+    constexpr int pos = u % SB;                          // a group starts at a multiple of RD, RD is a multiple of SB
+    const int cur = (kb / SB) & 1;
+    // prefetch: the next stage of A at the first block of a stage (to registers, then LDS), W RD - 1 blocks ahead
+    // (register ring); past the launch's last block the loads go against the empty descriptor
+    if (pos == 0) {
 #pragma unroll
-    for (int u = 0; u < RD; ++u) {
-      const int kb = kbase + u;
-      if (kb < nkb) {                                    // uniform
-        const int pos = u % SB;                          // a constant once unrolled: kbase is a multiple of RD, RD of SB
-        const int cur = (kb / SB) & 1;
-        // prefetch: the next stage of A at the first block of a stage (to registers, then LDS), W RD - 1 blocks ahead
-        // (register ring); past the launch's last block the loads go against the empty descriptor
-        if (pos == 0) {
+      for (int s = 0; s < SB; ++s) {
+        const __amdgpu_buffer_rsrc_t rs = GEMM_RS_A(kb + SB + s < nkb);
 #pragma unroll
-          for (int s = 0; s < SB; ++s) {
-            const __amdgpu_buffer_rsrc_t rs = GEMM_RS_A(kb + SB + s < nkb);
+        for (int i = 0; i < MI; ++i) areg[s][i] = GEMM_LDA(rs, i, min(kb + SB + s, nkb - 1));
+      }
+    }
+    {
+      const __amdgpu_buffer_rsrc_t rs = GEMM_RS_W(kb + RD - 1 < nkb);
 #pragma unroll
-            for (int i = 0; i < MI; ++i) areg[s][i] = GEMM_LDA(rs, i, min(kb + SB + s, nkb - 1));
-          }
-        }
-        {
-          const __amdgpu_buffer_rsrc_t rs = GEMM_RS_W(kb + RD - 1 < nkb);
+      for (int j = 0; j < 4; ++j) breg[(u + RD - 1) % RD][j] = GEMM_LDW(rs, min(kb + RD - 1, nkb - 1), j);
+    }
+    __builtin_amdgcn_sched_barrier(0);   // keep the prefetch loads ahead of this block's MFMAs
+    const uint16_t* al = a_lds[cur][pos] + a_frag;
 #pragma unroll
-          for (int j = 0; j < 4; ++j) breg[(u + RD - 1) % RD][j] = GEMM_LDW(rs, min(kb + RD - 1, nkb - 1), j);
-        }
-        __builtin_amdgcn_sched_barrier(0);   // keep the prefetch loads ahead of this block's MFMAs
-        const uint16_t* al = a_lds[cur][pos] + a_frag;
+    for (int j = 0; j < 4; ++j) {
+      const bf16x8_t bf = __builtin_bit_cast(bf16x8_t, breg[u][j]);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const bf16x8_t bf = __builtin_bit_cast(bf16x8_t, breg[u][j]);
+      for (int i = 0; i < MI; ++i) {
+        const u32x4 av = *(const u32x4*)(al + i * 32 * LDS_ROW + j * 8);
+        if (EPI >= 2) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf, __builtin_bit_cast(bf16x8_t, av), acc[i], 0, 0, 0);
+        else acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av), bf, acc[i], 0, 0, 0);
+      }
+    }
+    if (pos == SB - 1) {                                 // the stage is used up: publish the next one
 #pragma unroll
-          for (int i = 0; i < MI; ++i) {
-            const u32x4 av = *(const u32x4*)(al + i * 32 * LDS_ROW + j * 8);
-            if (EPI >= 2) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf, __builtin_bit_cast(bf16x8_t, av), acc[i], 0, 0, 0);
-            else acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av), bf, acc[i], 0, 0, 0);
-          }
-        }
-        if (pos == SB - 1) {                             // the stage is used up: publish the next one
+      for (int s = 0; s < SB; ++s)
 #pragma unroll
-          for (int s = 0; s < SB; ++s)
-#pragma unroll
-            for (int i = 0; i < MI; ++i) *(u32x4*)&a_lds[cur ^ 1][s][a_dst[i]] = areg[s][i];
-          __syncthreads();
-        }
+        for (int i = 0; i < MI; ++i) *(u32x4*)&a_lds[cur ^ 1][s][a_dst[i]] = areg[s][i];
+      __syncthreads();
+    }
+  };
+  // Full groups of RD blocks run without a test between the blocks (with an exit after every block the compiler's
+  // wait-count pass merges the states of all those paths and drains most of the W ring once per group); the last
+  // blocks follow, each behind its test.
+  static_assert(RD == 3 || RD == 4, "the group calls below are written out for a ring of 3 or 4");
+  int kbase = 0;
+  for (; kbase + RD <= nkb; kbase += RD) {
+    block(std::integral_constant<int, 0>{}, kbase);
+    block(std::integral_constant<int, 1>{}, kbase + 1);
+    block(std::integral_constant<int, 2>{}, kbase + 2);
+    if constexpr (RD == 4) block(std::integral_constant<int, 3>{}, kbase + 3);
+  }
+  if (kbase < nkb) {
+    block(std::integral_constant<int, 0>{}, kbase);
+    if (kbase + 1 < nkb) {
+      block(std::integral_constant<int, 1>{}, kbase + 1);
+      if constexpr (RD == 4) {
+        if (kbase + 2 < nkb) block(std::integral_constant<int, 2>{}, kbase + 2);
       }
     }
   }
@@ -290,6 +306,9 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16(const uint16_t* __restrict
 // The four tiles are four separate arrays on purpose: the compiler's wait-count pass tells in-flight LDS-direct loads
 // from LDS reads by the array they address, so fragment reads of one tile do not wait for the loads into another.
 #define DEEP_TILE (256 * 64)
+#ifndef DEEP_WAIT_VM
+#define DEEP_WAIT_VM 16
+#endif
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 template <int EPI>
 __global__ __launch_bounds__(256, 1) void k_gemm_bf16_deep(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
@@ -356,63 +375,79 @@ __global__ __launch_bounds__(256, 1) void k_gemm_bf16_deep(const uint16_t* __res
     for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
   u32x4 breg[4][4];   // W ring; every index is a compile-time constant after unrolling
   u32x4 af[2][8];     // A fragments of the current and the next k-step
-  // prologue: A blocks 0..2 into tiles 0..2, W blocks 0..2
-#pragma unroll
-  for (int b = 0; b < 3; ++b) {
-    const __amdgpu_buffer_rsrc_t rs = DEEP_RS_A(b < nkb);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) DEEP_LDA(rs, b, i, min(b, nkb - 1));
-  }
+  // prologue: W blocks 0..2, then A blocks 0..2 into tiles 0..2; everything has landed when the loop starts, so the
+  // loop is entered in the state its own iterations leave behind
 #pragma unroll
   for (int r = 0; r < 3; ++r) {
     const __amdgpu_buffer_rsrc_t rs = DEEP_RS_W(r < nkb);
 #pragma unroll
     for (int j = 0; j < 4; ++j) breg[r][j] = DEEP_LDW(rs, min(r, nkb - 1), j);
   }
-  __builtin_amdgcn_s_waitcnt(0x0F70 | 12);   // vmcnt(12): the 24 A loads have landed, the 12 W loads may still fly
+#pragma unroll
+  for (int b = 0; b < 3; ++b) {
+    const __amdgpu_buffer_rsrc_t rs = DEEP_RS_A(b < nkb);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) DEEP_LDA(rs, b, i, min(b, nkb - 1));
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
   __syncthreads();
 #pragma unroll
   for (int i = 0; i < 8; ++i) af[0][i] = *(const u32x4*)(a0 + a_frag[0] + i * 32 * 64);
 
-  for (int kbase = 0; kbase < nkb; kbase += 4) {
+  // one k block; u = kb % 4 is a compile-time constant (ring slot and LDS tile)
+  auto block = [&](auto uc, const int kb) __attribute__((always_inline)) {
+    constexpr int u = decltype(uc)::value;
+    const uint16_t* al = DEEP_SEL(u % 4);
+    const uint16_t* al_next = DEEP_SEL((u + 1) % 4);
+    const int k3 = min(kb + 3, nkb - 1);
+    const __amdgpu_buffer_rsrc_t a_rs3 = DEEP_RS_A(kb + 3 < nkb), w_rs3 = DEEP_RS_W(kb + 3 < nkb);
+    // k-step 0: + A block kb+3 straight into tile (kb+3) % 4 (last read before the previous barrier)
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int kb = kbase + u;
-      if (kb < nkb) {                                    // uniform
-        const uint16_t* al = DEEP_SEL(u % 4);
-        const uint16_t* al_next = DEEP_SEL((u + 1) % 4);
-        const int k3 = min(kb + 3, nkb - 1);
-        const __amdgpu_buffer_rsrc_t a_rs3 = DEEP_RS_A(kb + 3 < nkb), w_rs3 = DEEP_RS_W(kb + 3 < nkb);
-        // k-step 0: + A block kb+3 straight into tile (kb+3) % 4 (last read before the previous barrier)
+    for (int i = 0; i < 8; ++i) af[1][i] = *(const u32x4*)(al + a_frag[1] + i * 32 * 64);
+    DEEP_MFMA8(af[0], __builtin_bit_cast(bf16x8_t, breg[u % 4][0]));
 #pragma unroll
-        for (int i = 0; i < 8; ++i) af[1][i] = *(const u32x4*)(al + a_frag[1] + i * 32 * 64);
-        DEEP_MFMA8(af[0], __builtin_bit_cast(bf16x8_t, breg[u % 4][0]));
+    for (int i = 0; i < 8; ++i) DEEP_LDA(a_rs3, (u + 3) % 4, i, k3);
+    DEEP_PIN(1)
+    // k-step 1
 #pragma unroll
-        for (int i = 0; i < 8; ++i) DEEP_LDA(a_rs3, (u + 3) % 4, i, k3);
-        DEEP_PIN(1)
-        // k-step 1
+    for (int i = 0; i < 8; ++i) af[0][i] = *(const u32x4*)(al + a_frag[2] + i * 32 * 64);
+    DEEP_MFMA8(af[1], __builtin_bit_cast(bf16x8_t, breg[u % 4][1]));
+    DEEP_PIN(0)
+    // k-step 2: + W block kb+3
 #pragma unroll
-        for (int i = 0; i < 8; ++i) af[0][i] = *(const u32x4*)(al + a_frag[2] + i * 32 * 64);
-        DEEP_MFMA8(af[1], __builtin_bit_cast(bf16x8_t, breg[u % 4][1]));
-        DEEP_PIN(0)
-        // k-step 2: + W block kb+3
+    for (int i = 0; i < 8; ++i) af[1][i] = *(const u32x4*)(al + a_frag[3] + i * 32 * 64);
+    DEEP_MFMA8(af[0], __builtin_bit_cast(bf16x8_t, breg[u % 4][2]));
 #pragma unroll
-        for (int i = 0; i < 8; ++i) af[1][i] = *(const u32x4*)(al + a_frag[3] + i * 32 * 64);
-        DEEP_MFMA8(af[0], __builtin_bit_cast(bf16x8_t, breg[u % 4][2]));
+    for (int j = 0; j < 4; ++j) breg[(u + 3) % 4][j] = DEEP_LDW(w_rs3, k3, j);
+    DEEP_PIN(2)
+    // k-step 3: first fragments of block kb+1 (published one barrier ago)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) breg[(u + 3) % 4][j] = DEEP_LDW(w_rs3, k3, j);
-        DEEP_PIN(2)
-        // k-step 3: first fragments of block kb+1 (published one barrier ago)
-#pragma unroll
-        for (int i = 0; i < 8; ++i) af[0][i] = *(const u32x4*)(al_next + a_frag[0] + i * 32 * 64);
-        DEEP_MFMA8(af[1], __builtin_bit_cast(bf16x8_t, breg[u % 4][3]));
-        DEEP_PIN(0)
-        // block kb+2 (its A loads were issued one iteration ago) must have landed before this barrier publishes it;
-        // only this iteration's 8 A + 4 W loads are newer
-        __builtin_amdgcn_s_waitcnt(0x0F70 | 12);
-        __builtin_amdgcn_s_barrier();          // no fence: a release fence would wait for this iteration's loads too
-        __builtin_amdgcn_sched_barrier(0);
-      }
+    for (int i = 0; i < 8; ++i) af[0][i] = *(const u32x4*)(al_next + a_frag[0] + i * 32 * 64);
+    DEEP_MFMA8(af[1], __builtin_bit_cast(bf16x8_t, breg[u % 4][3]));
+    DEEP_PIN(0)
+    // the A tile of block kb+2 (loads issued one iteration ago) must have landed before this barrier publishes it:
+    // its first fragments are read during the next iteration's last k-step.  Loads complete in issue order -- A then
+    // W in every iteration -- so only the W loads of that iteration (block kb+2, not needed for another two
+    // iterations; the compiler waits for those registers itself) and this iteration's 8 A + 4 W loads may still fly
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (DEEP_WAIT_VM & 15) | ((DEEP_WAIT_VM >> 4) << 14));
+    __builtin_amdgcn_s_barrier();          // no fence: a release fence would wait for this iteration's loads too
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  // Full groups of four blocks run without a test between the blocks: with an exit after every block the compiler's
+  // wait-count pass merges the states of all those paths and ends up draining the load queue (vmcnt 0..4) at the top of
+  // two blocks in four.  The last one to three blocks follow, each behind its test.
+  int kbase = 0;
+  for (; kbase + 4 <= nkb; kbase += 4) {
+    block(std::integral_constant<int, 0>{}, kbase);
+    block(std::integral_constant<int, 1>{}, kbase + 1);
+    block(std::integral_constant<int, 2>{}, kbase + 2);
+    block(std::integral_constant<int, 3>{}, kbase + 3);
+  }
+  if (kbase < nkb) {
+    block(std::integral_constant<int, 0>{}, kbase);
+    if (kbase + 1 < nkb) {
+      block(std::integral_constant<int, 1>{}, kbase + 1);
+      if (kbase + 2 < nkb) block(std::integral_constant<int, 2>{}, kbase + 2);
     }
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);   // the loads issued past the last block have completed before LDS is given up
@@ -647,9 +682,6 @@ __global__ void k_reduce_splits(const float* __restrict__ part, float* __restric
 // Number of K splits: enough workgroups to cover the chip's 256 CUs without drowning the weight stream
 // in partial-sum traffic.
 int gemm_pick_splits(int M, int N, int K) {
-#ifdef GEMM_SPLIT_SWEEP
-  if (const char* e = getenv("GEMM_S")) { const int nkb_ = K / GEMM_BK, S_ = atoi(e); const int per_ = (nkb_ + S_ - 1) / S_; return (nkb_ + per_ - 1) / per_; }
-#endif
   // Never more workgroups than the chip has CUs: a launch of 280-320 workgroups puts a second one on some CUs, which
   // then set its length (QKV at 8-128 rows: 6 splits = 288 workgroups 15.9-29.4 us, 5 splits = 240 workgroups 13.4-25.5 us;
   // the 32B shapes at 64 rows likewise).  At most 8 splits (partial-sum traffic), and with up to 128 rows at least 10 k
