@@ -438,17 +438,31 @@ __global__ __launch_bounds__(64 * PF_KSPLIT, 2) void k_prefill_attn(const uint8_
       }
     }
   };
+  // Page ids run one tile further ahead than the fragments: pg holds the pages of the tile whose fragments are fetched
+  // during the current iteration, pg2 those of the tile after it, requested at the top of the iteration.  Loads complete
+  // in issue order, so an id requested right before it is used would make its user wait for every V load in flight (that
+  // was a full drain of the queue between the score product and the softmax of every tile).  The prologue issues its loads
+  // in the order an iteration leaves them in -- id, K fragments, V fragments -- so that the wait counts the compiler
+  // derives for the loop are those of the steady state.
+  int pg2 = 0;
   if (w < n_kt) {                                          // uniform
-    pg = pt[min(w * 2 + (c >> 4), last_page)];
-    const uint8_t* kb = pool + ((size_t)pg * Hkv + kvh) * BLK + (c & 15) * 16 + g * 256;
+    const int pg0 = pt[min(w * 2 + (c >> 4), last_page)];
+    const int kt1 = w + PF_KSPLIT < n_kt ? w + PF_KSPLIT : w;
+    pg = pt[min(kt1 * 2 + (c >> 4), last_page)];
+    __builtin_amdgcn_sched_barrier(0);
+    const uint8_t* kb = pool + ((size_t)pg0 * Hkv + kvh) * BLK + (c & 15) * 16 + g * 256;
 #pragma unroll
     for (int dc = 0; dc < NDC; ++dc) kf[dc] = *(const u32x4*)(kb + dc * 512);
-    load_v(pg, vw);
+    __builtin_amdgcn_sched_barrier(0);
+    load_v(pg0, vw);
+    __builtin_amdgcn_sched_barrier(0);
   }
   for (int kt = w; kt < n_kt; kt += PF_KSPLIT) {
     const int ktn = kt + PF_KSPLIT < n_kt ? kt + PF_KSPLIT : kt;   // past the end: this tile once more
+    const int kt2 = ktn + PF_KSPLIT < n_kt ? ktn + PF_KSPLIT : ktn;
     const int kn = ktn * 32 + c;
-    pg = pt[min(kn >> 4, last_page)];                               // (its latency hides behind the score MFMAs)
+    pg2 = pt[min(kt2 * 2 + (c >> 4), last_page)];
+    __builtin_amdgcn_sched_barrier(0);
     f32x16_t s;
 #pragma unroll
     for (int j = 0; j < 16; ++j) s[j] = 0.f;
@@ -518,6 +532,7 @@ __global__ __launch_bounds__(64 * PF_KSPLIT, 2) void k_prefill_attn(const uint8_
         o[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vw[s2][mt]), pf, o[mt], 0, 0, 0);
     }
     load_v(pg, vw);                                      // the next tile's V fragments, into the registers just consumed
+    pg = pg2;
   }
 
   // ---- merge the wavefronts' partial results: 2 -> 0 and 3 -> 1, then 1 -> 0 (lane-local: every wavefront keeps the
