@@ -111,9 +111,12 @@ __global__ __launch_bounds__(64 * ATTN_GROUP) void k_decode_attn(
           vr[j][half][dd] = ld_stream16(vb + ((size_t)half * D + dim) * 16);
         }
     }
-    // keep them up front: left alone, the scheduler sinks the V loads below the score phase to save registers (three
-    // wavefronts per SIMD instead of two, but two memory round trips per tile instead of one; 0.5 % slower in the step)
-    __builtin_amdgcn_sched_barrier(0);
+    // With up to four query heads per kv head they are kept up front: left alone, the scheduler sinks the V loads below
+    // the score phase to save registers (three wavefronts per SIMD instead of two, but two memory round trips per tile
+    // instead of one): 0.6 % slower on a full batch of the 8B shape, 0.5 % faster on its half batch, no difference in
+    // the tail drain.  With five heads per kv head (the 32B shape, 64 rows) the third wavefront is worth more than the
+    // round trip: pinned, its launches take 102-104 us instead of 97-99.
+    if constexpr (G <= 4) __builtin_amdgcn_sched_barrier(0);
     // ---- scores -----------------------------------------------------------------------------------------
     const bool valid = tok < tok_end;
 #pragma unroll
