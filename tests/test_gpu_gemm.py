@@ -26,6 +26,23 @@ def test_gemm_random_shapes(seed):
     _check_gemm(M, N, K)
 
 
+@pytest.mark.parametrize("M,N,kernel", [
+    (8, 384, "k_gemm_bf16<1,0,true>"), (40, 384, "k_gemm_bf16<2,0,true>"), (100, 384, "k_gemm_bf16<4,0,true>"),
+    (200, 384, "k_gemm_bf16_deep<0>"), (600, 384, "k_gemm_bf16_deep<0>"), (256, 33024, "k_gemm_bf16<8,0,true>"),
+    (600, 12000, "k_gemm_bf16_big<0,"),
+])
+def test_gemm_every_loop_tail(M, N, kernel):
+    """The k loops run full groups of ring-depth blocks (and, for the activation tile, stages of several blocks) without
+    a test between the blocks, then the last one to three blocks behind theirs, and prefetches past the last block go
+    against an empty buffer descriptor: every k-block count from 1 to 13 (all remainders of 3- and 4-deep rings, stages
+    ending inside a group, launches shorter than the prologue) on each kernel variant."""
+    import paper_2603_23414_amd as R
+    for nkb in range(1, 14):
+        K = 64 * nkb
+        assert R.rollout_gemm_kernel_name(M, N, K).startswith(kernel), (nkb, R.rollout_gemm_kernel_name(M, N, K))
+        _check_gemm(M, N, K)
+
+
 def _check_gemm(M, N, K):
     import torch
     import paper_2603_23414_amd as R

@@ -109,6 +109,10 @@ def test_projection_shapes_of_the_timed_step(M, N, K, kernel):
     (256, 48, 64, "k_gemm_bf16_deep<1>"),            # one k block, one partly filled column tile
     (64, 27648, 5120, "k_gemm_bf16<2,1,true>"),      # the 32B gate/up projection at its batch
     (24, 512, 128, "k_gemm_bf16<1,1,true>"),
+    (8, 512, 64 * 9, "k_gemm_bf16<1,1,true>"),       # k-block counts that end inside a ring group and inside an activation stage
+    (40, 512, 64 * 6, "k_gemm_bf16<2,1,true>"),
+    (100, 512, 64 * 7, "k_gemm_bf16<4,1,true>"),
+    (200, 512, 64 * 7, "k_gemm_bf16_deep<1>"),
     (700, 14336, 512, "k_gemm_bf16_big<1,3,true>"),  # several row blocks (prefill)
 ])
 def test_swiglu_projection_against_float64(M, F, K, kernel):
