@@ -9,6 +9,15 @@
 // is loaded global -> LDS directly, so that the 16-byte fragment reads are bank-conflict free).  Split-K over
 // blockIdx.z writes fp32 partial sums that the consumer kernels (residual+norm, RoPE, SiLU*mul) add up in a
 // fixed order, so results are deterministic.
+//
+// Two things about the k loops that the timings depend on and the source does not otherwise show:
+//  - the compiler's wait-count pass merges the load-queue states of every path into a block.  A loop that may leave
+//    after every block of its unrolled ring, or a prologue that issues its loads in another order than an iteration
+//    does, makes it wait for (nearly) the whole queue at the top of some blocks.  So the loops run full groups of blocks
+//    with no test in between, handle the last few blocks separately, and the prologues mimic an iteration's order;
+//  - prefetches that would reach past a launch's last k block are issued against a buffer descriptor with zero records
+//    (the range check then returns zeros without a memory access, and the load still counts in vmcnt), which keeps the
+//    loops free of conditional loads without fetching the last block again and again.
 #include <cstdio>
 #include <type_traits>
 
@@ -25,10 +34,6 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // processing in the texture path, not HBM, LDS or MFMA).  Rows are padded with zeros to a multiple of 32.
 #define WTILE_ELEMS 2048   // bf16 elements per (nt, kb) tile
 
-template <bool STREAM>
-__device__ __forceinline__ u32x4 ldw(const uint16_t* p) {
-  return STREAM ? __builtin_nontemporal_load((const u32x4*)p) : *(const u32x4*)p;
-}
 #ifndef GEMM_STAGE_MI1      // k blocks per activation stage of k_gemm_bf16 at 32 / 64 / 128 rows
 #define GEMM_STAGE_MI1 4
 #endif
@@ -47,7 +52,7 @@ __device__ __forceinline__ u32x4 ldw(const uint16_t* p) {
 // in blocks of 16 (cols 32q..32q+15 = gate of features 16q.., cols 32q+16..32q+31 = up of the same features), the
 // two halves of a wave's 32 columns meet through one cross-lane exchange, and bf16 silu(gate)*up goes to
 // act[M, N/2].  No split-K in that mode.
-// STREAM = true reads W with streaming (non-temporal) loads: right when every weight byte is used once per launch
+// STREAM = true reads W with streaming loads (the nt bit of the buffer load): right when every weight byte is used once per launch
 // (M <= 256), wrong when several row blocks re-read the same W slab from L2 (prefill).
 // EPI = 2 (greedy) / 3 (sampling): the LM head with the emit statistics in its epilogue (no logits are stored).  The two MFMA operands are
 // swapped, which transposes the accumulator tile at no cost (both fragments have the same register layout): a lane
