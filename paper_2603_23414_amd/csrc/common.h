@@ -6,11 +6,14 @@
 #define PAGE_TOKENS 16
 // A decode-attention wavefront covers `chunk` cached tokens of one (row, kv head), a workgroup ATTN_GROUP_CHUNKS
 // consecutive chunks (one work item of the list); the chunk is chosen per launch: a multiple of 64 between
-// ATTN_CHUNK_MIN and ATTN_CHUNK_MAX, about (sum of contexts) * n_kv_heads / ATTN_TARGET_ITEMS, i.e. roughly five
-// rounds of wavefronts over the chip's resident ones (measured: 481 us at two rounds, 469 at three, 465 at four, 461
-// at five to eight; with little context in flight the floor of 128 tokens beats 256 by 5 % and 64 loses again):
-// fine enough that the end of the launch stays busy, and small in the tail drain so that a few long rollouts still
-// spread over the chip.
+// ATTN_CHUNK_MIN and ATTN_CHUNK_MAX, about (sum of contexts) * n_kv_heads / ATTN_TARGET_ITEMS wavefront spans, i.e.
+// the largest chunks that still leave every resident wavefront slot (256 CUs x 4 SIMDs x 2) a span or two: with the
+// rows finished inside the kernel and the work list ordered longest-first, fewer and longer items win (fewer partial
+// results, fewer workgroup starts).  Measured, attention alone, us per launch at 12288 / 6144 / 4096 spans: 32 rows of
+// 4-16 k tokens 240 / 228 / 229, 64 rows 390 / 377 / 378, a full batch 457 / 446 / 445; in the step 454.6 / 451.4 /
+// 451.0 (full batch), 558 / 548 / 548 (123 rows), 247 / 240 / 237 (32 rows); 9 long rows and the 32B workload's 64 short
+// ones sit at the 128-token floor either way (the floor beats 256 by 5 % there and 64 loses again), so that a few long
+// rollouts still spread over the chip.
 #ifndef ATTN_GROUP_CHUNKS
 #define ATTN_GROUP_CHUNKS 4
 #endif
@@ -19,7 +22,7 @@
 #endif
 #define ATTN_CHUNK_MAX 1024         // 64 pages: their ids fit one register across a wavefront
 #ifndef ATTN_TARGET_ITEMS
-#define ATTN_TARGET_ITEMS 12288     // 256 CUs x 4 SIMDs x 3 resident waves x 4 rounds
+#define ATTN_TARGET_ITEMS 4096
 #endif
 __host__ __device__ __forceinline__ int attn_pick_chunk(unsigned long long total_ctx, int n_kv_heads) {
   unsigned long long c = (total_ctx * (unsigned long long)n_kv_heads + ATTN_TARGET_ITEMS - 1) / ATTN_TARGET_ITEMS;
