@@ -375,8 +375,13 @@ void launch_write_kv(void* pool, int Hkv, int head_dim, const void* k, const voi
 // Both products are taken transposed so that a lane always owns one query row:
 //   S^T = K Q^T   (A = K tile straight from the page: lane -> key, 16-byte dim chunks; B = Q^T in registers)
 //   O^T = V^T P^T (A = V^T straight from the page: lane -> dim, token runs; B = P^T = the softmaxed S^T
-//                  accumulators, whose register order already is the k order the V loads use)
+//                  accumulators)
 // which keeps the online-softmax statistics, the rescaling and the final 1/l entirely lane-local.
+// The accumulator layout of S^T gives a half-wave, per page, score rows {4g..4g+3} and {8+4g..8+4g+3} (g = lane / 32),
+// while the value product wants from it the probabilities of eight CONSECUTIVE tokens (the run one 16-byte V load
+// holds).  So the K rows are fetched in a permuted order -- the lane that feeds score row r loads the key whose token
+// index within its page is r with bits 2 and 3 swapped -- which makes the rows a half-wave owns exactly tokens 8g..8g+7
+// of each page: the P^T operand is then the packed accumulators as they are, and every V fragment is one 16-byte load.
 struct PfTile { int row0, n, slot, pos0; };
 
 // PF_KSPLIT wavefronts share one (query tile, head): wavefront w takes key tiles w, w + PF_KSPLIT, ..  A query tile deep
@@ -408,6 +413,8 @@ __global__ __launch_bounds__(64 * PF_KSPLIT, 2) void k_prefill_attn(const uint8_
   const int last_key = tile.pos0 + tile.n - 1;
   const int last_page = last_key >> 4;
   const int* __restrict__ pt = page_table + (size_t)tile.slot * max_pages;
+  // token (within its page) of the key this lane loads for score row c: bits 2 and 3 of c swapped
+  const int tau = (c & 3) | ((c & 4) << 1) | ((c & 8) >> 1);
 
   bf16x8_t qf[NDC];
   {
@@ -434,13 +441,11 @@ __global__ __launch_bounds__(64 * PF_KSPLIT, 2) void k_prefill_attn(const uint8_
 #pragma unroll
     for (int s2 = 0; s2 < 2; ++s2) {
       const int pgs = __builtin_amdgcn_readlane(pg_t, s2 * 16);
-      const uint8_t* vb = pool + ((size_t)pgs * Hkv + kvh) * BLK + KBYTES + g * 8;
+      const uint8_t* vb = pool + ((size_t)pgs * Hkv + kvh) * BLK + KBYTES + (size_t)g * D * 16;
 #pragma unroll
       for (int mt = 0; mt < NMT; ++mt) {
         const int dim = mt * 32 + c;
-        const u32x2 lo = *(const u32x2*)(vb + (size_t)dim * 16);
-        const u32x2 hi = *(const u32x2*)(vb + (size_t)(D + dim) * 16);
-        v[s2][mt].x = lo.x; v[s2][mt].y = lo.y; v[s2][mt].z = hi.x; v[s2][mt].w = hi.y;
+        v[s2][mt] = *(const u32x4*)(vb + (size_t)dim * 16);    // tokens 8g .. 8g+7 of the page, one dim
       }
     }
   };
@@ -456,7 +461,7 @@ __global__ __launch_bounds__(64 * PF_KSPLIT, 2) void k_prefill_attn(const uint8_
     const int kt1 = w + PF_KSPLIT < n_kt ? w + PF_KSPLIT : w;
     pg = pt[min(kt1 * 2 + (c >> 4), last_page)];
     __builtin_amdgcn_sched_barrier(0);
-    const uint8_t* kb = pool + ((size_t)pg0 * Hkv + kvh) * BLK + (c & 15) * 16 + g * 256;
+    const uint8_t* kb = pool + ((size_t)pg0 * Hkv + kvh) * BLK + tau * 16 + g * 256;
 #pragma unroll
     for (int dc = 0; dc < NDC; ++dc) kf[dc] = *(const u32x4*)(kb + dc * 512);
     __builtin_amdgcn_sched_barrier(0);
@@ -466,7 +471,6 @@ __global__ __launch_bounds__(64 * PF_KSPLIT, 2) void k_prefill_attn(const uint8_
   for (int kt = w; kt < n_kt; kt += PF_KSPLIT) {
     const int ktn = kt + PF_KSPLIT < n_kt ? kt + PF_KSPLIT : kt;   // past the end: this tile once more
     const int kt2 = ktn + PF_KSPLIT < n_kt ? ktn + PF_KSPLIT : ktn;
-    const int kn = ktn * 32 + c;
     pg2 = pt[min(kt2 * 2 + (c >> 4), last_page)];
     __builtin_amdgcn_sched_barrier(0);
     f32x16_t s;
@@ -476,18 +480,18 @@ __global__ __launch_bounds__(64 * PF_KSPLIT, 2) void k_prefill_attn(const uint8_
     for (int dc = 0; dc < NDC; ++dc)
       s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[dc]), qf[dc], s, 0, 0, 0);
     {   // the next tile's K fragments go into the registers the score product has just consumed
-      const uint8_t* kb = pool + ((size_t)pg * Hkv + kvh) * BLK + (kn & 15) * 16 + g * 256;
+      const uint8_t* kb = pool + ((size_t)pg * Hkv + kvh) * BLK + tau * 16 + g * 256;
 #pragma unroll
       for (int dc = 0; dc < NDC; ++dc) kf[dc] = *(const u32x4*)(kb + dc * 512);
     }
-    // s[j] = score of key kt*32 + (j/4)*8 + g*4 + j%4 against this lane's query row.  Only key tiles that reach past
+    // s[j] = score of key kt*32 + (j/8)*16 + g*8 + j%8 against this lane's query row (K rows are loaded permuted).  Only key tiles that reach past
     // the tile's first query need the causal mask (the last one or two); the others are wholly visible.
     const bool diag = kt * 32 + 31 > tile.pos0;           // wave-uniform
     float mx = NEG_BIG;
     if (diag) {
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
-        const int key = kt * 32 + (j >> 2) * 8 + g * 4 + (j & 3);
+        const int key = kt * 32 + (j >> 3) * 16 + g * 8 + (j & 7);   // score row (j/4)*8 + 4g + j%4 holds this key (see tau)
         s[j] = key <= pos_c ? s[j] * scale_log2e : NEG_BIG;
         mx = fmaxf(mx, s[j]);
       }
