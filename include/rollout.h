@@ -220,8 +220,8 @@ uint64_t rollout_attn_workspace_bytes(uint32_t n, uint64_t total_ctx, uint32_t n
 
 /* Build the work list for context lengths ctx_len (host int32 [n], each >= 1) at the head of workspace_dev: one item
  * (one workgroup per kv head) per four consecutive chunks of a sequence.  The chunk (cached tokens per wavefront, a
- * multiple of 64 in 128..1024) is chosen from the total context so that the wavefronts make about five rounds over
- * the chip; it is returned in chunk_tokens and must be passed to rollout_attn_decode; n_work receives the number
+ * multiple of 64 in 128..1024) is chosen from the total context as the largest that still leaves every resident
+ * wavefront slot of the chip a span or two; it is returned in chunk_tokens and must be passed to rollout_attn_decode; n_work receives the number
  * of items.  Also zeroes the per-(sequence, kv head) arrival counters with which the work items of a long sequence
  * find out which of them finishes last and merges their partial results; every rollout_attn_decode leaves them at
  * zero again, so one plan serves any number of launches -- but launches that overlap in time must not share a
